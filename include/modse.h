@@ -1,0 +1,139 @@
+/*
+ * modse.h - C ABI of the MI355X (gfx950) library for one Mixture-of-Diverse-
+ * Size-Experts (MoDSE) FFN layer, arXiv 2409.12210.
+ *
+ * The layer (Sec. 2 Eq. 1-3 and Sec. 3.1 of the paper):
+ *     logits  H(x)_i = (x W_gate)_i (+ logit_bias_i)
+ *     gate    G(x)   = Softmax(KeepTopK(H(x), top_k))         (Eq. 2, Eq. 3)
+ *     output  y      = sum_i G_i(x) E_i(x)                     (Eq. 1; Sec. 3.1)
+ *     expert  E_i(x) = W2_i ( silu(W1_i x) * (W3_i x) ),  W1_i,W3_i in R^{d_ff[i] x d},
+ *                      W2_i in R^{d x d_ff[i]}                 (Llama-2 FFN, Sec. 4.1)
+ * Each expert has its own hidden width d_ff[i] (Sec. 3.1).  Ties in top-k go to
+ * the lower expert index; no token is ever dropped.
+ *
+ * Conventions for every call
+ *  - "HOST" / "DEVICE" says where a pointer must point.  The library allocates
+ *    and frees nothing: all buffers, workspace included, belong to the caller.
+ *  - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream).  They never synchronise and never read device
+ *    memory from the host.
+ *  - All argument checks run before the first enqueue and need no GPU.
+ *    Errors are reported through the return code only.
+ *  - T == 0 is valid and does nothing (pointers are then not examined).
+ *  - NaN/Inf inputs: behaviour unspecified.
+ *
+ * Layouts (row-major everywhere, element type = desc.dtype unless said):
+ *    x, y, dY, dX   [T, d_model]
+ *    W_gate         [d_model, n_experts]
+ *    W1, W3         one [F, d_model] matrix, F = sum d_ff; expert e owns rows
+ *                   foff[e] .. foff[e+1]-1, foff[e] = sum_{e'<e} d_ff[e']
+ *    W2             expert e starts at element d_model*foff[e] and is a
+ *                   [d_model, d_ff[e]] matrix
+ *    dW_gate, dW1, dW3, dW2   float32, same shapes as the weights
+ */
+#ifndef MODSE_H_
+#define MODSE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MODSE_OK = 0,
+  MODSE_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad d_ff, ... */
+  MODSE_ERR_UNSUPPORTED = 2, /* top_k not in {1,2}, n_experts > 64, unknown dtype */
+  MODSE_ERR_WORKSPACE = 3,   /* ws_bytes smaller than modse_workspace_size() */
+  MODSE_ERR_HIP = 4          /* a HIP launch failed */
+} modse_status;
+
+typedef enum { MODSE_F32 = 0, MODSE_BF16 = 1 } modse_dtype;
+
+/* Layer description.  Plain HOST struct, read during the call only. */
+typedef struct {
+  int32_t d_model;      /* multiple of 32 */
+  int32_t n_experts;    /* N, 1..64 */
+  int32_t top_k;        /* 1 or 2, <= N */
+  const int32_t* d_ff;  /* HOST array [n_experts]; each > 0 and a multiple of 32;
+                           any order, pairs are not assumed (Sec. 3.1 pair
+                           constraint is the caller's business) */
+  modse_dtype dtype;    /* element type of x, weights, y, dY, dX */
+} modse_desc;
+
+/* Routing artefacts, all DEVICE pointers, caller-allocated.  Permuted row r of
+ * expert e lies in offsets[e] <= r < offsets[e+1]; inside an expert rows keep
+ * ascending token order. */
+typedef struct {
+  int32_t* topk_idx;       /* [T, top_k] expert ids, slot 0 = largest logit */
+  float* topk_w;           /* [T, top_k] gate weights (Eq. 2), sum to 1 per token */
+  int32_t* counts;         /* [N] tokens*slots per expert */
+  int32_t* offsets;        /* [N+1] exclusive prefix sum of counts */
+  int32_t* row_of;         /* [T, top_k] (token, slot) -> permuted row */
+  int32_t* src_of;         /* [T*top_k] permuted row -> token*top_k + slot */
+  int32_t* near_tie_count; /* [1] tokens with a gap < 1e-6 between two neighbouring
+                              logits among their top_k+1 largest */
+} modse_routing;
+
+/* Bytes of DEVICE workspace `ws` that modse_route / modse_layer_fwd
+ * (need_bwd = 0) or modse_layer_bwd (need_bwd = 1) require for T tokens. */
+modse_status modse_workspace_size(const modse_desc* desc, int64_t T, int need_bwd, size_t* bytes);
+
+/* Bytes of the DEVICE buffer `saved` that carries activations from
+ * modse_layer_fwd to modse_layer_bwd (pre-activations W1 x and W3 x, the hidden
+ * activations and the expert outputs, all in permuted row order). */
+modse_status modse_saved_size(const modse_desc* desc, int64_t T, size_t* bytes);
+
+/* Router only: logits, top-k, gate weights (Eq. 2-3) and the stable permutation
+ * by expert.  x [T,d] DEVICE, W_gate [d,N] DEVICE, logit_bias [N] float32
+ * DEVICE or NULL.  Fills every field of *out. */
+modse_status modse_route(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                         const float* logit_bias, const modse_routing* out, void* ws, size_t ws_bytes,
+                         void* hip_stream);
+
+/* Forward pass of the layer (Eq. 1 with diverse-size experts, Sec. 3.1):
+ * route, permute, grouped up-projection with SwiGLU, grouped down-projection,
+ * gate-weighted combine.  y [T,d] DEVICE out.  routing_out may be NULL unless
+ * a backward pass follows; saved may be NULL unless a backward pass follows. */
+modse_status modse_layer_fwd(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                             const float* logit_bias, const void* W1, const void* W3, const void* W2, void* y,
+                             const modse_routing* routing_out, void* saved, void* ws, size_t ws_bytes,
+                             void* hip_stream);
+
+/* Backward pass (chain rule through Eq. 1-3; logits outside the kept set get
+ * zero gradient).  routing and saved are the ones modse_layer_fwd filled for
+ * the same inputs.  dY [T,d] DEVICE in.  Outputs: dX [T,d] (desc.dtype),
+ * dW_gate [d,N], dW1 [F,d], dW3 [F,d], dW2 (packed like W2), all float32.
+ * accumulate = 0 overwrites the weight gradients, 1 adds to them (fp32
+ * gradient accumulation); dX is always overwritten. */
+modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, const void* W_gate, const void* W1,
+                             const void* W3, const void* W2, const modse_routing* routing, const void* saved,
+                             const void* dY, void* dX, float* dW_gate, float* dW1, float* dW3, float* dW2,
+                             int accumulate, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Per-stage timing for benchmarks.  When enabled, modse_layer_fwd/bwd record
+ * HIP events between their stages on the caller's stream; modse_stage_times
+ * waits for the last recorded call and returns milliseconds per stage
+ * (HOST array of MODSE_N_STAGES floats; stages not run read 0). */
+enum {
+  MODSE_STAGE_ROUTE = 0,    /* router GEMM + top-k + gate */
+  MODSE_STAGE_PERMUTE = 1,  /* histogram, scan, scatter, tile plan */
+  MODSE_STAGE_UP = 2,       /* grouped W1/W3 GEMM + SwiGLU */
+  MODSE_STAGE_DOWN = 3,     /* grouped W2 GEMM */
+  MODSE_STAGE_COMBINE = 4,  /* gate-weighted unpermute */
+  MODSE_STAGE_BWD_PREP = 5, /* dO, d gate, transposes */
+  MODSE_STAGE_BWD_DGRAD = 6,/* dH (+SwiGLU backward) and dX_permuted GEMMs */
+  MODSE_STAGE_BWD_WGRAD = 7,/* dW1, dW3, dW2 GEMMs */
+  MODSE_STAGE_BWD_ROUTER = 8,/* dX gather, d logits, dW_gate */
+  MODSE_N_STAGES = 9
+};
+modse_status modse_stage_timing_enable(int on);
+modse_status modse_stage_times(float* ms);
+
+const char* modse_status_string(modse_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MODSE_H_ */

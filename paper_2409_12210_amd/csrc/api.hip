@@ -1,0 +1,406 @@
+// C ABI of libmodse: argument checks, workspace carving and the launch sequence of the MoDSE layer
+// (forward: route -> permute -> grouped up-GEMM + SwiGLU -> grouped down-GEMM -> combine; backward: the
+// chain rule through the same steps).  Nothing here allocates device memory or synchronises, except the
+// opt-in per-stage timing.
+#include <algorithm>
+#include <cstring>
+
+#include "common.h"
+
+namespace {
+
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  }
+};
+
+size_t esize_of(modse_dtype dt) { return dt == MODSE_F32 ? 4 : 2; }
+
+modse_status check_desc(const modse_desc* desc, int64_t T) {
+  if (!desc || !desc->d_ff) return MODSE_ERR_INVALID_ARG;
+  if (T < 0) return MODSE_ERR_INVALID_ARG;
+  if (desc->dtype != MODSE_F32 && desc->dtype != MODSE_BF16) return MODSE_ERR_UNSUPPORTED;
+  if (desc->n_experts < 1 || desc->d_model < 1) return MODSE_ERR_INVALID_ARG;
+  if (desc->top_k < 1 || desc->top_k > desc->n_experts) return MODSE_ERR_INVALID_ARG;
+  if (desc->n_experts > MODSE_MAX_EXPERTS) return MODSE_ERR_UNSUPPORTED;
+  if (desc->top_k > 2) return MODSE_ERR_UNSUPPORTED;
+  if (desc->d_model % 32 != 0) return MODSE_ERR_INVALID_ARG;
+  int64_t fmax = 0;
+  for (int e = 0; e < desc->n_experts; ++e) {
+    const int32_t f = desc->d_ff[e];
+    if (f <= 0 || f % 32 != 0) return MODSE_ERR_INVALID_ARG;
+    fmax = std::max<int64_t>(fmax, f);
+  }
+  // kernels index rows and per-expert matrices with 32-bit element offsets
+  const int64_t lim = (int64_t)1 << 31;
+  if (T * desc->top_k + 64 * desc->n_experts + 64 >= lim / 64) return MODSE_ERR_UNSUPPORTED;
+  if ((T + 64) * std::max<int64_t>(fmax, desc->d_model) >= lim) return MODSE_ERR_UNSUPPORTED;
+  if (fmax * desc->d_model >= lim) return MODSE_ERR_UNSUPPORTED;
+  return MODSE_OK;
+}
+
+LayerDims make_dims(const modse_desc* desc, int64_t T) {
+  LayerDims L;
+  std::memset(&L, 0, sizeof(L));
+  L.d = desc->d_model;
+  L.N = desc->n_experts;
+  L.k = desc->top_k;
+  L.T = (int32_t)T;
+  for (int e = 0; e < L.N; ++e) {
+    L.f[e] = desc->d_ff[e];
+    L.foff[e + 1] = L.foff[e] + L.f[e];
+    L.order[e] = e;
+  }
+  std::stable_sort(L.order, L.order + L.N, [&](int a, int b) { return L.f[a] > L.f[b]; });
+  L.ldt = (int32_t)(align_up((size_t)T * L.k, MODSE_KPAD) + (size_t)MODSE_KPAD * L.N);
+  return L;
+}
+
+// Upper bound of sum_e n_e * d_ff[e]: every token picks top_k distinct experts, so at worst all tokens
+// pick the top_k widest ones.
+size_t hidden_elems_max(const LayerDims& L) {
+  size_t s = 0;
+  for (int j = 0; j < L.k; ++j) s += (size_t)L.f[L.order[j]];
+  return s * (size_t)L.T;
+}
+
+struct FwdLayout {
+  size_t blockhist, topk_idx, topk_w, counts, offsets, row_of, src_of, near_tie, plan_up, plan_down, Xp, H, O, total;
+};
+
+FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
+  FwdLayout w;
+  Carver c;
+  const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k;
+  const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
+  w.blockhist = c.take(nb * (L.N + 1) * 4);
+  w.topk_idx = c.take(Tk * 4);
+  w.topk_w = c.take(Tk * 4);
+  w.counts = c.take(L.N * 4);
+  w.offsets = c.take((L.N + 1) * 4);
+  w.row_of = c.take(Tk * 4);
+  w.src_of = c.take(Tk * 4);
+  w.near_tie = c.take(4);
+  w.plan_up = c.take(sizeof(GemmPlan));
+  w.plan_down = c.take(sizeof(GemmPlan));
+  w.Xp = c.take(Tk * L.d * es);
+  w.H = c.take(hidden_elems_max(L) * es);
+  w.O = c.take(Tk * L.d * es);
+  w.total = c.off;
+  return w;
+}
+
+struct SavedLayout {
+  size_t Apre, Bpre, H, O, total;
+};
+
+SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
+  SavedLayout s;
+  Carver c;
+  const size_t es = esize_of(dt), h = hidden_elems_max(L) * es;
+  s.Apre = c.take(h);
+  s.Bpre = c.take(h);
+  s.H = c.take(h);
+  s.O = c.take((size_t)L.T * L.k * L.d * es);
+  s.total = c.off;
+  return s;
+}
+
+struct BwdLayout {
+  size_t plan[6], W1T, W3T, W2T, Xp, XpT, dO, dOT, HT, dA, dB, dAT, dBT, dXp, dg, dWg_partial, total;
+};
+
+BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
+  BwdLayout w;
+  Carver c;
+  const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k, F = L.foff[L.N];
+  const size_t h = hidden_elems_max(L) * es;
+  const size_t hp = (hidden_elems_max(L) + (size_t)MODSE_KPAD * F) * es;  // token axis padded per expert
+  const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
+  for (int i = 0; i < 6; ++i) w.plan[i] = c.take(sizeof(GemmPlan));
+  w.W1T = c.take(F * L.d * es);
+  w.W3T = c.take(F * L.d * es);
+  w.W2T = c.take(F * L.d * es);
+  w.Xp = c.take(Tk * L.d * es);
+  w.XpT = c.take((size_t)L.d * L.ldt * es);
+  w.dO = c.take(Tk * L.d * es);
+  w.dOT = c.take((size_t)L.d * L.ldt * es);
+  w.HT = c.take(hp);
+  w.dA = c.take(h);
+  w.dB = c.take(h);
+  w.dAT = c.take(hp);
+  w.dBT = c.take(hp);
+  w.dXp = c.take(Tk * L.d * es);
+  w.dg = c.take(Tk * 4);
+  w.dWg_partial = c.take(nb * L.d * L.N * 4);
+  w.total = c.off;
+  return w;
+}
+
+int64_t tiles_bound(const LayerDims& L, int64_t rows_max, const TileShape& t, bool n_is_f) {
+  int64_t s = 0;
+  for (int e = 0; e < L.N; ++e) {
+    const int64_t nt = ((n_is_f ? L.f[e] : L.d) + t.bn - 1) / t.bn;
+    s += ((rows_max + t.bm - 1) / t.bm) * nt;
+  }
+  return s;
+}
+
+// ---------------------------------------------------------------- stage timing
+struct StageTimer {
+  bool on = false;
+  static constexpr int MAXEV = 24;
+  hipEvent_t ev[2][MAXEV];
+  int stage[2][MAXEV];
+  int n[2] = {0, 0};
+  bool created = false;
+};
+StageTimer g_timer;
+
+struct Stamp {
+  int which;
+  hipStream_t s;
+  bool on;
+  Stamp(int w, hipStream_t st) : which(w), s(st), on(g_timer.on) {
+    if (on) {
+      g_timer.n[which] = 0;
+      mark(-1);
+    }
+  }
+  void mark(int stage) {
+    if (!on) return;
+    int& n = g_timer.n[which];
+    if (n >= StageTimer::MAXEV) return;
+    g_timer.stage[which][n] = stage;
+    (void)hipEventRecord(g_timer.ev[which][n], s);
+    ++n;
+  }
+};
+
+#define HIP_TRY(expr)                            \
+  do {                                           \
+    if ((expr) != hipSuccess) return MODSE_ERR_HIP; \
+  } while (0)
+
+RoutingPtrs routing_from(const modse_routing* r, char* ws, const FwdLayout& w) {
+  RoutingPtrs R;
+  if (r) {
+    R = {r->topk_idx, r->topk_w, r->counts, r->offsets, r->row_of, r->src_of, r->near_tie_count};
+  } else {
+    R = {reinterpret_cast<int32_t*>(ws + w.topk_idx), reinterpret_cast<float*>(ws + w.topk_w),
+         reinterpret_cast<int32_t*>(ws + w.counts),   reinterpret_cast<int32_t*>(ws + w.offsets),
+         reinterpret_cast<int32_t*>(ws + w.row_of),   reinterpret_cast<int32_t*>(ws + w.src_of),
+         reinterpret_cast<int32_t*>(ws + w.near_tie)};
+  }
+  return R;
+}
+
+bool routing_complete(const modse_routing* r) {
+  return r && r->topk_idx && r->topk_w && r->counts && r->offsets && r->row_of && r->src_of && r->near_tie_count;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* modse_status_string(modse_status s) {
+  switch (s) {
+    case MODSE_OK: return "ok";
+    case MODSE_ERR_INVALID_ARG: return "invalid argument";
+    case MODSE_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MODSE_ERR_WORKSPACE: return "workspace too small";
+    case MODSE_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+modse_status modse_workspace_size(const modse_desc* desc, int64_t T, int need_bwd, size_t* bytes) {
+  if (!bytes) return MODSE_ERR_INVALID_ARG;
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  const LayerDims L = make_dims(desc, T);
+  *bytes = need_bwd ? bwd_layout(L, desc->dtype).total : fwd_layout(L, desc->dtype).total;
+  return MODSE_OK;
+}
+
+modse_status modse_saved_size(const modse_desc* desc, int64_t T, size_t* bytes) {
+  if (!bytes) return MODSE_ERR_INVALID_ARG;
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  *bytes = saved_layout(make_dims(desc, T), desc->dtype).total;
+  return MODSE_OK;
+}
+
+modse_status modse_route(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                         const float* logit_bias, const modse_routing* out, void* ws, size_t ws_bytes,
+                         void* hip_stream) {
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  if (T == 0) return MODSE_OK;
+  if (!x || !W_gate || !ws || !routing_complete(out)) return MODSE_ERR_INVALID_ARG;
+  const LayerDims L = make_dims(desc, T);
+  const FwdLayout w = fwd_layout(L, desc->dtype);
+  if (ws_bytes < w.total) return MODSE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* wsb = static_cast<char*>(ws);
+  const RoutingPtrs R = routing_from(out, wsb, w);
+  HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
+                       nullptr, s));
+  return MODSE_OK;
+}
+
+modse_status modse_layer_fwd(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                             const float* logit_bias, const void* W1, const void* W3, const void* W2, void* y,
+                             const modse_routing* routing_out, void* saved, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  if (T == 0) return MODSE_OK;
+  if (!x || !W_gate || !W1 || !W3 || !W2 || !y || !ws) return MODSE_ERR_INVALID_ARG;
+  if (routing_out && !routing_complete(routing_out)) return MODSE_ERR_INVALID_ARG;
+  const modse_dtype dt = desc->dtype;
+  const LayerDims L = make_dims(desc, T);
+  const FwdLayout w = fwd_layout(L, dt);
+  if (ws_bytes < w.total) return MODSE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* wsb = static_cast<char*>(ws);
+  const RoutingPtrs R = routing_from(routing_out, wsb, w);
+  Stamp stamp(0, s);
+
+  void* Xp = wsb + w.Xp;
+  HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist), Xp, s));
+  stamp.mark(MODSE_STAGE_ROUTE);  // routing and the row scatter share kernels; the scatter is counted here
+
+  FwdPlanArgs pa;
+  std::memset(&pa, 0, sizeof(pa));
+  pa.Xp = Xp; pa.W1 = W1; pa.W3 = W3; pa.W2 = W2;
+  if (saved) {
+    const SavedLayout sl = saved_layout(L, dt);
+    char* sb = static_cast<char*>(saved);
+    pa.Apre = sb + sl.Apre; pa.Bpre = sb + sl.Bpre; pa.H = sb + sl.H; pa.O = sb + sl.O;
+  } else {
+    pa.H = wsb + w.H; pa.O = wsb + w.O;
+  }
+  pa.up = reinterpret_cast<GemmPlan*>(wsb + w.plan_up);
+  pa.down = reinterpret_cast<GemmPlan*>(wsb + w.plan_down);
+  pa.up_tile = gemm_tile_shape(dt, EPI_SWIGLU, T);
+  pa.down_tile = gemm_tile_shape(dt, EPI_STORE, T);
+  HIP_TRY(launch_plan_fwd(L, dt, R.counts, R.offsets, pa, s));
+  stamp.mark(MODSE_STAGE_PERMUTE);
+
+  HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU, pa.up, 0, saved != nullptr, tiles_bound(L, T, pa.up_tile, true), s));
+  stamp.mark(MODSE_STAGE_UP);
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE, pa.down, 0, 0, tiles_bound(L, T, pa.down_tile, false), s));
+  stamp.mark(MODSE_STAGE_DOWN);
+  HIP_TRY(launch_combine(L, dt, pa.O, R, y, s));
+  stamp.mark(MODSE_STAGE_COMBINE);
+  return MODSE_OK;
+}
+
+modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, const void* W_gate, const void* W1,
+                             const void* W3, const void* W2, const modse_routing* routing, const void* saved,
+                             const void* dY, void* dX, float* dW_gate, float* dW1, float* dW3, float* dW2,
+                             int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  if (T == 0) return MODSE_OK;
+  if (!x || !W_gate || !W1 || !W3 || !W2 || !saved || !dY || !dX || !dW_gate || !dW1 || !dW3 || !dW2 || !ws)
+    return MODSE_ERR_INVALID_ARG;
+  if (!routing_complete(routing)) return MODSE_ERR_INVALID_ARG;
+  const modse_dtype dt = desc->dtype;
+  const LayerDims L = make_dims(desc, T);
+  const BwdLayout w = bwd_layout(L, dt);
+  if (ws_bytes < w.total) return MODSE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* wsb = static_cast<char*>(ws);
+  const SavedLayout sl = saved_layout(L, dt);
+  const char* sb = static_cast<const char*>(saved);
+  const RoutingPtrs R = {routing->topk_idx, routing->topk_w, routing->counts, routing->offsets,
+                         routing->row_of,   routing->src_of, routing->near_tie_count};
+  Stamp stamp(1, s);
+
+  void* Xp = wsb + w.Xp;
+  void* dO = wsb + w.dO;
+  float* dg = reinterpret_cast<float*>(wsb + w.dg);
+  HIP_TRY(launch_gather_rows(L, dt, x, R, Xp, s));
+  HIP_TRY(launch_bwd_prep(L, dt, dY, sb + sl.O, R, dO, dg, s));
+  HIP_TRY(launch_transpose_weights(L, dt, W1, W3, W2, wsb + w.W1T, wsb + w.W3T, wsb + w.W2T, s));
+  HIP_TRY(launch_transpose_act(L, dt, 0, R.counts, R.offsets, Xp, wsb + w.XpT, s));
+  HIP_TRY(launch_transpose_act(L, dt, 0, R.counts, R.offsets, dO, wsb + w.dOT, s));
+  HIP_TRY(launch_transpose_act(L, dt, 1, R.counts, R.offsets, sb + sl.H, wsb + w.HT, s));
+
+  BwdPlanArgs pa;
+  std::memset(&pa, 0, sizeof(pa));
+  pa.dO = dO; pa.Apre = sb + sl.Apre; pa.Bpre = sb + sl.Bpre;
+  pa.W1T = wsb + w.W1T; pa.W3T = wsb + w.W3T; pa.W2T = wsb + w.W2T;
+  pa.XpT = wsb + w.XpT; pa.dOT = wsb + w.dOT; pa.HT = wsb + w.HT; pa.dAT = wsb + w.dAT; pa.dBT = wsb + w.dBT;
+  pa.dA = wsb + w.dA; pa.dB = wsb + w.dB; pa.dXp = wsb + w.dXp;
+  pa.dW1 = dW1; pa.dW3 = dW3; pa.dW2 = dW2;
+  pa.dh = reinterpret_cast<GemmPlan*>(wsb + w.plan[0]);
+  pa.dx = reinterpret_cast<GemmPlan*>(wsb + w.plan[1]);
+  pa.wg1 = reinterpret_cast<GemmPlan*>(wsb + w.plan[2]);
+  pa.wg3 = reinterpret_cast<GemmPlan*>(wsb + w.plan[3]);
+  pa.wg2 = reinterpret_cast<GemmPlan*>(wsb + w.plan[4]);
+  pa.dh_tile = gemm_tile_shape(dt, EPI_SWIGLU_BWD, T);
+  pa.dx_tile = gemm_tile_shape(dt, EPI_STORE_DUALK, T);
+  pa.wg_tile = gemm_tile_shape(dt, EPI_STORE_F32, T);
+  HIP_TRY(launch_plan_bwd(L, dt, R.counts, R.offsets, pa, s));
+  stamp.mark(MODSE_STAGE_BWD_PREP);
+
+  HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU_BWD, pa.dh, 0, 0, tiles_bound(L, T, pa.dh_tile, true), s));
+  stamp.mark(MODSE_STAGE_BWD_DGRAD);
+  HIP_TRY(launch_transpose_act(L, dt, 1, R.counts, R.offsets, pa.dA, wsb + w.dAT, s));
+  HIP_TRY(launch_transpose_act(L, dt, 1, R.counts, R.offsets, pa.dB, wsb + w.dBT, s));
+  stamp.mark(MODSE_STAGE_BWD_PREP);
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_DUALK, pa.dx, 0, 0, tiles_bound(L, T, pa.dx_tile, false), s));
+  stamp.mark(MODSE_STAGE_BWD_DGRAD);
+
+  int64_t fmax = L.f[L.order[0]];
+  const int64_t wg13 = tiles_bound(L, fmax, pa.wg_tile, false);
+  const int64_t wg2 = tiles_bound(L, L.d, pa.wg_tile, true);
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg1, accumulate, 0, wg13, s));
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg3, accumulate, 0, wg13, s));
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg2, accumulate, 0, wg2, s));
+  stamp.mark(MODSE_STAGE_BWD_WGRAD);
+
+  HIP_TRY(launch_bwd_router(L, dt, x, W_gate, pa.dXp, dg, R, dX, reinterpret_cast<float*>(wsb + w.dWg_partial),
+                            dW_gate, accumulate, s));
+  stamp.mark(MODSE_STAGE_BWD_ROUTER);
+  return MODSE_OK;
+}
+
+modse_status modse_stage_timing_enable(int on) {
+  if (on && !g_timer.created) {
+    for (int w = 0; w < 2; ++w)
+      for (int i = 0; i < StageTimer::MAXEV; ++i)
+        if (hipEventCreate(&g_timer.ev[w][i]) != hipSuccess) return MODSE_ERR_HIP;
+    g_timer.created = true;
+  }
+  g_timer.on = on != 0;
+  g_timer.n[0] = g_timer.n[1] = 0;
+  return MODSE_OK;
+}
+
+modse_status modse_stage_times(float* ms) {
+  if (!ms) return MODSE_ERR_INVALID_ARG;
+  for (int i = 0; i < MODSE_N_STAGES; ++i) ms[i] = 0.f;
+  if (!g_timer.created) return MODSE_OK;
+  for (int w = 0; w < 2; ++w) {
+    const int n = g_timer.n[w];
+    if (n < 2) continue;
+    if (hipEventSynchronize(g_timer.ev[w][n - 1]) != hipSuccess) return MODSE_ERR_HIP;
+    for (int i = 1; i < n; ++i) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, g_timer.ev[w][i - 1], g_timer.ev[w][i]) != hipSuccess) return MODSE_ERR_HIP;
+      const int st = g_timer.stage[w][i];
+      if (st >= 0 && st < MODSE_N_STAGES) ms[st] += t;
+    }
+  }
+  return MODSE_OK;
+}
+
+}  // extern "C"

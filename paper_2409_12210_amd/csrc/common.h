@@ -1,0 +1,177 @@
+// Internal declarations shared by the translation units of libmodse (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "modse.h"
+
+#define MODSE_MAX_EXPERTS 64
+#define MODSE_ROUTE_TOKENS_PER_BLOCK 32  // tokens handled by one block of the router / scatter kernels
+#define MODSE_KPAD 64                    // token-axis padding of transposed activations (backward)
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- element helpers
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr modse_dtype dtype = MODSE_F32;
+};
+template <>
+struct Elem<bf16_t> {
+  static constexpr modse_dtype dtype = MODSE_BF16;
+};
+
+// 8 consecutive elements -> 8 floats
+__device__ inline void load8(const float* p, float v[8]) {
+  const f32x4 a = *reinterpret_cast<const f32x4*>(p);
+  const f32x4 b = *reinterpret_cast<const f32x4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ inline void load8(const bf16_t* p, float v[8]) {
+  const bf16x8 a = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+}
+__device__ inline void store8(float* p, const float v[8]) {
+  f32x4 a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+  *reinterpret_cast<f32x4*>(p) = a;
+  *reinterpret_cast<f32x4*>(p + 4) = b;
+}
+__device__ inline void store8(bf16_t* p, const float v[8]) {
+  bf16x8 a;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = (bf16_t)v[i];
+  *reinterpret_cast<bf16x8*>(p) = a;
+}
+__device__ inline void load4(const float* p, float v[4]) {
+  const f32x4 a = *reinterpret_cast<const f32x4*>(p);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+}
+__device__ inline void load4(const bf16_t* p, float v[4]) {
+  const bf16x4 a = *reinterpret_cast<const bf16x4*>(p);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = (float)a[i];
+}
+__device__ inline void store4(float* p, const float v[4]) {
+  f32x4 a = {v[0], v[1], v[2], v[3]};
+  *reinterpret_cast<f32x4*>(p) = a;
+}
+__device__ inline void store4(bf16_t* p, const float v[4]) {
+  bf16x4 a;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = (bf16_t)v[i];
+  *reinterpret_cast<bf16x4*>(p) = a;
+}
+
+// ---------------------------------------------------------------- grouped GEMM
+// One problem per expert:  C[M,N] (+)= A[M,K] B[N,K]^T (+ A2[M,K] B2[N,K]^T), operands with K contiguous.
+struct GemmProblem {
+  const void* A;
+  const void* B;
+  const void* A2;  // second operand pair of a K-concatenated product (dX = dA W1 + dB W3), or null
+  const void* B2;  // second B matrix: W3 of the up-projection (two accumulators) or pair of A2
+  void* C;
+  void* C2;        // extra outputs of fused epilogues
+  void* C3;
+  const void* E1;  // extra epilogue inputs
+  const void* E2;
+  int32_t M, N, K;
+  int32_t lda, ldb, ldc;
+  int32_t mtiles, ntiles;
+  int32_t pad0;
+};
+
+struct GemmPlan {
+  GemmProblem prob[MODSE_MAX_EXPERTS];
+  int32_t tile_start[MODSE_MAX_EXPERTS + 1];  // prefix sum of mtiles*ntiles in problem order
+  int32_t n_prob;
+  int32_t pad[2];
+};
+
+enum GemmEpilogue {
+  EPI_STORE = 0,       // C = acc (element type of the layer)
+  EPI_STORE_F32 = 1,   // C = acc or C += acc, float32 (weight gradients)
+  EPI_SWIGLU = 2,      // two accumulators a, b: C = silu(a)*b; optionally C2 = a, C3 = b
+  EPI_SWIGLU_BWD = 3,  // acc = dh; E1 = a, E2 = b: C = da, C2 = db
+  EPI_STORE_DUALK = 4, // C = acc over two operand pairs (A,B) and (A2,B2)
+};
+
+// Host-known description of the layer handed to kernels by value.
+struct LayerDims {
+  int32_t d, N, k;
+  int32_t T;
+  int32_t f[MODSE_MAX_EXPERTS];
+  int32_t foff[MODSE_MAX_EXPERTS + 1];
+  int32_t order[MODSE_MAX_EXPERTS];  // experts by descending width (ties: lower index)
+  int32_t ldt;                       // row stride of token-transposed activations (backward)
+};
+
+struct RoutingPtrs {
+  int32_t* topk_idx;
+  float* topk_w;
+  int32_t* counts;
+  int32_t* offsets;
+  int32_t* row_of;
+  int32_t* src_of;
+  int32_t* near_tie_count;
+};
+
+// ---------------------------------------------------------------- launchers
+// route.hip
+hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
+                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, hipStream_t s);
+hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, const RoutingPtrs& R, void* y,
+                          hipStream_t s);
+hipError_t launch_bwd_prep(const LayerDims& L, modse_dtype dt, const void* dY, const void* O, const RoutingPtrs& R,
+                           void* dO, float* dg, hipStream_t s);
+hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, void* Xp,
+                              hipStream_t s);
+hipError_t launch_bwd_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const void* dXp,
+                             const float* dg, const RoutingPtrs& R, void* dX, float* dWg_partial, float* dW_gate,
+                             int accumulate, hipStream_t s);
+
+// gemm.hip
+struct TileShape {
+  int32_t bm, bn;
+};
+TileShape gemm_tile_shape(modse_dtype dt, int epilogue, int64_t T);
+hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* plan, int accumulate, int save_pre,
+                               int64_t max_tiles, hipStream_t s);
+
+struct FwdPlanArgs {
+  const void *Xp, *W1, *W3, *W2;
+  void *H, *Apre, *Bpre, *O;  // Apre/Bpre may be null
+  GemmPlan *up, *down;
+  TileShape up_tile, down_tile;
+};
+hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
+                           const FwdPlanArgs& a, hipStream_t s);
+
+struct BwdPlanArgs {
+  const void *dO, *Apre, *Bpre;
+  const void *W1T, *W3T, *W2T;            // transposed weights
+  const void *XpT, *dOT, *HT, *dAT, *dBT;  // token-transposed activations, K padded to MODSE_KPAD per expert
+  void *dA, *dB, *dXp;
+  float *dW1, *dW3, *dW2;
+  GemmPlan *dh, *dx, *wg1, *wg3, *wg2;
+  TileShape dh_tile, dx_tile, wg_tile;
+};
+hipError_t launch_plan_bwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
+                           const BwdPlanArgs& a, hipStream_t s);
+
+// Transposes.  Weights: per expert, host-known shapes.  Activations: rows per expert are counts[e] (device
+// side); destination columns are padded with zeros up to a multiple of MODSE_KPAD.
+hipError_t launch_transpose_weights(const LayerDims& L, modse_dtype dt, const void* W1, const void* W3,
+                                    const void* W2, void* W1T, void* W3T, void* W2T, hipStream_t s);
+// kind 0: dense [T*k, d] -> [d, ldt];  kind 1: ragged per expert [n_e, f_e] -> [f_e, npad_e]
+hipError_t launch_transpose_act(const LayerDims& L, modse_dtype dt, int kind, const int32_t* counts,
+                                const int32_t* offsets, const void* src, void* dst, hipStream_t s);

@@ -1,0 +1,602 @@
+// Ragged grouped GEMMs of the MoDSE layer on gfx950: one problem per expert, M = tokens routed to the
+// expert (known only on the device), N or K = the expert's own hidden width d_ff[e] (Sec. 3.1 of
+// arXiv 2409.12210).  A tiny plan kernel turns the device-side counts into a problem table and a tile
+// prefix; persistent GEMM workgroups walk the tile list without any host round trip.
+#include "common.h"
+
+namespace {
+
+constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;  // tiles of GROUP_M consecutive row blocks are walked column-first (L2 reuse)
+
+struct TileCoord {
+  int p, mt, nt;
+};
+
+__device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, TileCoord& tc) {
+  const int np = plan->n_prob;
+  int p = 0;
+  while (p < np && tile >= plan->tile_start[p + 1]) ++p;
+  if (p >= np) return false;
+  const int local = tile - plan->tile_start[p];
+  const int mtiles = plan->prob[p].mtiles, ntiles = plan->prob[p].ntiles;
+  const int per_group = GROUP_M * ntiles;
+  const int first = (local / per_group) * GROUP_M;
+  const int gsz = min(mtiles - first, GROUP_M);
+  const int rem = local % per_group;
+  tc.p = p;
+  tc.mt = first + rem % gsz;
+  tc.nt = rem / gsz;
+  return true;
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of the tile list so
+// that the tiles sharing operand rows meet in the same L2.
+__device__ inline int first_tile_of_block() {
+  const int G = gridDim.x, b = blockIdx.x;
+  return (G % NUM_XCD == 0) ? (b % NUM_XCD) * (G / NUM_XCD) + b / NUM_XCD : b;
+}
+
+__device__ inline float silu_f(float a) { return a / (1.f + __expf(-a)); }
+
+// Epilogue on 4 consecutive columns n..n+3 of row m.  a = first accumulator, b = second (SwiGLU only).
+template <typename T, int EPI>
+__device__ inline void epilogue4(const GemmProblem& P, int m, int n, const float a[4], const float b[4],
+                                 int accumulate, int save_pre) {
+  if (m >= P.M || n >= P.N) return;
+  const size_t o = (size_t)m * P.ldc + n;
+  if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
+    store4(static_cast<T*>(P.C) + o, a);
+  } else if constexpr (EPI == EPI_STORE_F32) {
+    float* c = static_cast<float*>(P.C) + o;
+    float v[4] = {a[0], a[1], a[2], a[3]};
+    if (accumulate) {
+      float old[4];
+      load4(c, old);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] += old[i];
+    }
+    store4(c, v);
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    float h[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = silu_f(a[i]) * b[i];
+    store4(static_cast<T*>(P.C) + o, h);
+    if (save_pre) {
+      store4(static_cast<T*>(P.C2) + o, a);
+      store4(static_cast<T*>(P.C3) + o, b);
+    }
+  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+    float av[4], bv[4], da[4], db[4];
+    load4(static_cast<const T*>(P.E1) + o, av);
+    load4(static_cast<const T*>(P.E2) + o, bv);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float sig = 1.f / (1.f + __expf(-av[i]));
+      da[i] = a[i] * bv[i] * sig * (1.f + av[i] * (1.f - sig));
+      db[i] = a[i] * av[i] * sig;
+    }
+    store4(static_cast<T*>(P.C) + o, da);
+    store4(static_cast<T*>(P.C2) + o, db);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// float32 path: plain FMA tiles (parity configuration; no throughput claim)
+// ------------------------------------------------------------------------------------------------
+template <int EPI>
+__global__ __launch_bounds__(256) void gg_f32_kernel(const GemmPlan* __restrict__ plan, int accumulate,
+                                                     int save_pre) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[NB][BK][BN + 4];
+  const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  const int lrow = tid / 4, lk = (tid % 4) * 4;
+  const int total = plan->tile_start[plan->n_prob];
+  for (int tile = first_tile_of_block(); tile < total; tile += gridDim.x) {
+    TileCoord tc;
+    if (!decode_tile(plan, tile, tc)) break;
+    const GemmProblem P = plan->prob[tc.p];
+    const int m0 = tc.mt * BM, n0 = tc.nt * BN;
+    float acc[NB][4][4];
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[q][i][j] = 0.f;
+    const int arow = min(m0 + lrow, P.M - 1), brow = min(n0 + lrow, P.N - 1);
+    const int npass = (EPI == EPI_STORE_DUALK) ? 2 : 1;
+    for (int pass = 0; pass < npass; ++pass) {
+      const float* A = static_cast<const float*>(pass ? P.A2 : P.A) + (size_t)arow * P.lda + lk;
+      const float* B = static_cast<const float*>(pass ? P.B2 : P.B) + (size_t)brow * P.ldb + lk;
+      const float* B2 = NB == 2 ? static_cast<const float*>(P.B2) + (size_t)brow * P.ldb + lk : nullptr;
+      for (int k0 = 0; k0 < P.K; k0 += BK) {
+        const f32x4 av = *reinterpret_cast<const f32x4*>(A + k0);
+        const f32x4 bv = *reinterpret_cast<const f32x4*>(B + k0);
+        f32x4 b2v = {0.f, 0.f, 0.f, 0.f};
+        if (NB == 2) b2v = *reinterpret_cast<const f32x4*>(B2 + k0);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          As[lk + i][lrow] = av[i];
+          Bs[0][lk + i][lrow] = bv[i];
+          if (NB == 2) Bs[NB - 1][lk + i][lrow] = b2v[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < BK; ++k) {
+          float a[4], b[NB][4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+          for (int q = 0; q < NB; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[q][j] = Bs[q][k][tx * 4 + j];
+#pragma unroll
+          for (int q = 0; q < NB; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+              for (int j = 0; j < 4; ++j) acc[q][i][j] = fmaf(a[i], b[q][j], acc[q][i][j]);
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      epilogue4<float, EPI>(P, m0 + ty * 4 + i, n0 + tx * 4, acc[0][i], acc[NB - 1][i], accumulate, save_pre);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 path: MFMA 32x32x16 tiles, fp32 accumulate, LDS double buffer
+// ------------------------------------------------------------------------------------------------
+// Tile BM x BN (x NB matrices B sharing A), K step 64.  LDS rows are 128 bytes (64 bf16 along K); the
+// 16-byte chunk index is XOR-ed with (row & 7) so that the 32 rows a fragment read touches spread over
+// all banks.  The accumulator of v_mfma_f32_32x32x16_bf16 holds, per lane, 4 consecutive rows of the
+// instruction's first operand; feeding the B tile as first operand makes those 4 values consecutive
+// columns of C, stored as one 8- or 16-byte vector.
+template <int BM, int BN, int NB, int WM, int WN, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gg_bf16_kernel(const GemmPlan* __restrict__ plan,
+                                                                             int accumulate, int save_pre) {
+  constexpr int BK = 64;
+  constexpr int WAVES_N = BN / WN;
+  constexpr int NT = (BM / WM) * WAVES_N * 64;
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int CA = BM * 8 / NT;        // 16-byte chunks of the A tile per thread
+  constexpr int CB = NB * BN * 8 / NT;   // ... of the B tile(s)
+  constexpr int STAGE = (BM + NB * BN) * 128;
+  static_assert(BM * 8 % NT == 0 && NB * BN * 8 % NT == 0, "tile/thread mismatch");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int total = plan->tile_start[plan->n_prob];
+
+  for (int tile = first_tile_of_block(); tile < total; tile += gridDim.x) {
+    TileCoord tc;
+    if (!decode_tile(plan, tile, tc)) break;
+    const GemmProblem P = plan->prob[tc.p];
+    const int m0 = tc.mt * BM, n0 = tc.nt * BN;
+
+    f32x16 acc[NB][MI][NI];
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
+
+    // per-thread chunk coordinates: chunk q -> row q/8, 16-byte column q%8
+    int offA[CA], offB[CB], ldsA[CA], ldsB[CB];
+#pragma unroll
+    for (int it = 0; it < CA; ++it) {
+      const int q = tid + it * NT, row = q >> 3, cc = q & 7;
+      offA[it] = min(m0 + row, P.M - 1) * P.lda + cc * 8;
+      ldsA[it] = row * 128 + ((cc ^ (row & 7)) << 4);
+    }
+#pragma unroll
+    for (int it = 0; it < CB; ++it) {
+      const int q = tid + it * NT, row = q >> 3, cc = q & 7;
+      const int brow = row % BN;  // row inside one B matrix
+      offB[it] = min(n0 + brow, P.N - 1) * P.ldb + cc * 8;
+      ldsB[it] = BM * 128 + row * 128 + ((cc ^ (row & 7)) << 4);
+    }
+    const int kcol = (tid & 7) * 8;  // this thread's K offset inside a 64-wide K tile (same for all its chunks)
+
+    const int nk = (P.K + BK - 1) / BK;
+    const int npass = (EPI == EPI_STORE_DUALK) ? 2 : 1;
+    const int nsteps = nk * npass;
+    uint4 ra[CA], rb[CB];
+
+    auto gload = [&](int step) {
+      const int pass = step >= nk ? 1 : 0;
+      const int k0 = (step - pass * nk) * BK;
+      const bool kin = k0 + kcol < P.K;
+      const bf16_t* A = static_cast<const bf16_t*>(pass ? P.A2 : P.A) + k0;
+      const bf16_t* B = static_cast<const bf16_t*>(pass ? P.B2 : P.B) + k0;
+      const bf16_t* B2 = static_cast<const bf16_t*>(P.B2) + k0;
+#pragma unroll
+      for (int it = 0; it < CA; ++it) {
+        ra[it] = kin ? *reinterpret_cast<const uint4*>(A + offA[it]) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int it = 0; it < CB; ++it) {
+        const int q = tid + it * NT;
+        const bf16_t* src = (NB == 2 && (q >> 3) >= BN) ? B2 : B;
+        rb[it] = kin ? *reinterpret_cast<const uint4*>(src + offB[it]) : make_uint4(0, 0, 0, 0);
+      }
+    };
+    auto lstore = [&](int buf) {
+      char* base = smem + buf * STAGE;
+#pragma unroll
+      for (int it = 0; it < CA; ++it) *reinterpret_cast<uint4*>(base + ldsA[it]) = ra[it];
+#pragma unroll
+      for (int it = 0; it < CB; ++it) *reinterpret_cast<uint4*>(base + ldsB[it]) = rb[it];
+    };
+
+    __syncthreads();  // previous tile's readers are done with both buffers
+    if (nsteps > 0) {
+      gload(0);
+      lstore(0);
+    }
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+      const int buf = step & 1;
+      if (step + 1 < nsteps) gload(step + 1);
+      const char* sA = smem + buf * STAGE;
+      const char* sB = sA + BM * 128;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int sw = (((kk * 2 + (lane >> 5)) ^ (lane & 7)) << 4);
+        bf16x8 af[MI], bfr[NB][NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+          af[i] = *reinterpret_cast<const bf16x8*>(sA + (wm * WM + i * 32 + (lane & 31)) * 128 + sw);
+#pragma unroll
+        for (int q = 0; q < NB; ++q)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+            bfr[q][j] = *reinterpret_cast<const bf16x8*>(sB + (q * BN + wn * WN + j * 32 + (lane & 31)) * 128 + sw);
+#pragma unroll
+        for (int q = 0; q < NB; ++q)
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+              acc[q][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[q][j], af[i], acc[q][i][j], 0, 0, 0);
+      }
+      if (step + 1 < nsteps) lstore(buf ^ 1);
+      __syncthreads();
+    }
+
+    // epilogue: lane holds, for register group g, columns n .. n+3 of row m
+    const int mrow = m0 + wm * WM + (lane & 31);
+    const int ncol = n0 + wn * WN + 4 * (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float a[4], b[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            a[q] = acc[0][i][j][g * 4 + q];
+            b[q] = acc[NB - 1][i][j][g * 4 + q];
+          }
+          epilogue4<bf16_t, EPI>(P, mrow + i * 32, ncol + j * 32 + g * 8, a, b, accumulate, save_pre);
+        }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// plan kernels (single block): device-side counts -> problem tables
+// ------------------------------------------------------------------------------------------------
+__device__ inline void finish_plan(GemmPlan* plan, int i, bool on, int n, int bm, int bn, int* s_tiles) {
+  if (on) {
+    GemmProblem& P = plan->prob[i];
+    P.mtiles = (P.M + bm - 1) / bm;
+    P.ntiles = (P.N + bn - 1) / bn;
+    s_tiles[i] = P.mtiles * P.ntiles;
+  }
+  __syncthreads();
+  if (i == 0) {
+    int run = 0;
+    for (int q = 0; q < n; ++q) {
+      plan->tile_start[q] = run;
+      run += s_tiles[q];
+    }
+    plan->tile_start[n] = run;
+    plan->n_prob = n;
+  }
+  __syncthreads();
+}
+
+__device__ inline const char* cadd(const void* p, size_t bytes) { return static_cast<const char*>(p) + bytes; }
+__device__ inline char* vadd(void* p, size_t bytes) { return p ? static_cast<char*>(p) + bytes : nullptr; }
+
+__global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
+                                                      const int32_t* __restrict__ offsets, FwdPlanArgs a) {
+  __shared__ int s_tiles[MODSE_MAX_EXPERTS];
+  const int i = threadIdx.x;
+  const bool on = i < L.N;
+  const int e = on ? L.order[i] : 0;
+  size_t hoff = 0;  // elements of H before expert e
+  for (int q = 0; q < e; ++q) hoff += (size_t)counts[q] * L.f[q];
+  const int n_e = counts[e], f = L.f[e], d = L.d;
+  const size_t es = esize;
+  if (on) {
+    GemmProblem P = {};
+    P.A = cadd(a.Xp, (size_t)offsets[e] * d * es);
+    P.B = cadd(a.W1, (size_t)L.foff[e] * d * es);
+    P.B2 = cadd(a.W3, (size_t)L.foff[e] * d * es);
+    P.C = vadd(a.H, hoff * es);
+    P.C2 = vadd(a.Apre, hoff * es);
+    P.C3 = vadd(a.Bpre, hoff * es);
+    P.M = n_e; P.N = f; P.K = d;
+    P.lda = d; P.ldb = d; P.ldc = f;
+    a.up->prob[i] = P;
+  }
+  finish_plan(a.up, i, on, L.N, a.up_tile.bm, a.up_tile.bn, s_tiles);
+  if (on) {
+    GemmProblem P = {};
+    P.A = cadd(a.H, hoff * es);
+    P.B = cadd(a.W2, (size_t)L.foff[e] * d * es);
+    P.C = vadd(a.O, (size_t)offsets[e] * d * es);
+    P.M = n_e; P.N = d; P.K = f;
+    P.lda = f; P.ldb = f; P.ldc = d;
+    a.down->prob[i] = P;
+  }
+  finish_plan(a.down, i, on, L.N, a.down_tile.bm, a.down_tile.bn, s_tiles);
+}
+
+__device__ inline int pad_tokens(int n) { return (n + MODSE_KPAD - 1) / MODSE_KPAD * MODSE_KPAD; }
+
+__global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
+                                                      const int32_t* __restrict__ offsets, BwdPlanArgs a) {
+  __shared__ int s_tiles[MODSE_MAX_EXPERTS];
+  const int i = threadIdx.x;
+  const bool on = i < L.N;
+  const int e = on ? L.order[i] : 0;
+  size_t hoff = 0, hpoff = 0, poff = 0;
+  for (int q = 0; q < e; ++q) {
+    hoff += (size_t)counts[q] * L.f[q];
+    hpoff += (size_t)pad_tokens(counts[q]) * L.f[q];
+    poff += pad_tokens(counts[q]);
+  }
+  const int n_e = counts[e], npad = pad_tokens(n_e), f = L.f[e], d = L.d;
+  const size_t es = esize;
+  const size_t woff = (size_t)L.foff[e] * d;  // element offset of expert e in W1/W3/W2 and their transposes
+  if (on) {  // dh = dO W2, fused SwiGLU backward -> dA, dB
+    GemmProblem P = {};
+    P.A = cadd(a.dO, (size_t)offsets[e] * d * es);
+    P.B = cadd(a.W2T, woff * es);  // [f, d]
+    P.C = vadd(a.dA, hoff * es);
+    P.C2 = vadd(a.dB, hoff * es);
+    P.E1 = cadd(a.Apre, hoff * es);
+    P.E2 = cadd(a.Bpre, hoff * es);
+    P.M = n_e; P.N = f; P.K = d;
+    P.lda = d; P.ldb = d; P.ldc = f;
+    a.dh->prob[i] = P;
+  }
+  finish_plan(a.dh, i, on, L.N, a.dh_tile.bm, a.dh_tile.bn, s_tiles);
+  if (on) {  // dXp = dA W1 + dB W3
+    GemmProblem P = {};
+    P.A = cadd(a.dA, hoff * es);
+    P.B = cadd(a.W1T, woff * es);  // [d, f]
+    P.A2 = cadd(a.dB, hoff * es);
+    P.B2 = cadd(a.W3T, woff * es);
+    P.C = vadd(a.dXp, (size_t)offsets[e] * d * es);
+    P.M = n_e; P.N = d; P.K = f;
+    P.lda = f; P.ldb = f; P.ldc = d;
+    a.dx->prob[i] = P;
+  }
+  finish_plan(a.dx, i, on, L.N, a.dx_tile.bm, a.dx_tile.bn, s_tiles);
+  for (int which = 0; which < 2; ++which) {  // dW1 = dA^T Xp, dW3 = dB^T Xp
+    if (on) {
+      GemmProblem P = {};
+      P.A = cadd(which ? a.dBT : a.dAT, hpoff * es);  // [f, npad]
+      P.B = cadd(a.XpT, poff * es);                   // [d, ldt]
+      P.C = (which ? a.dW3 : a.dW1) + woff;
+      P.M = f; P.N = d; P.K = npad;
+      P.lda = npad; P.ldb = L.ldt; P.ldc = d;
+      (which ? a.wg3 : a.wg1)->prob[i] = P;
+    }
+    finish_plan(which ? a.wg3 : a.wg1, i, on, L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
+  }
+  if (on) {  // dW2 = dO^T H
+    GemmProblem P = {};
+    P.A = cadd(a.dOT, poff * es);   // [d, ldt]
+    P.B = cadd(a.HT, hpoff * es);   // [f, npad]
+    P.C = a.dW2 + woff;
+    P.M = d; P.N = f; P.K = npad;
+    P.lda = L.ldt; P.ldb = npad; P.ldc = f;
+    a.wg2->prob[i] = P;
+  }
+  finish_plan(a.wg2, i, on, L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
+}
+
+// ------------------------------------------------------------------------------------------------
+// transposes (backward): 64x64 tiles through LDS
+// ------------------------------------------------------------------------------------------------
+// dst[c][r] = src[r][c] for r < rows, c < cols; dst columns rows..rows_pad-1 are zero-filled.
+template <typename T>
+__device__ inline void transpose_tile(const T* __restrict__ src, int lds, int rows, int cols, T* __restrict__ dst,
+                                      int ldd, int rows_pad, int r0, int c0) {
+  __shared__ T tile[64][65];
+  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;  // 256 threads
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < rows && c < cols) ? src[(size_t)r * lds + c] : (T)0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (c < cols && r < rows_pad) dst[(size_t)c * ldd + r] = tile[tx][i];
+  }
+}
+
+// weights: mode 0: W [F,d] row blocks [f_e, d] -> [d, f_e] at d*foff[e];  mode 1: the reverse
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_weights_kernel(LayerDims L, int mode, const T* __restrict__ src,
+                                                                T* __restrict__ dst) {
+  const int e = blockIdx.y;
+  const int rows = mode == 0 ? L.f[e] : L.d, cols = mode == 0 ? L.d : L.f[e];
+  const int ct = (cols + 63) / 64;
+  const int rt = blockIdx.x / ct, cti = blockIdx.x % ct;
+  if (rt * 64 >= rows) return;
+  const size_t off = (size_t)L.foff[e] * L.d;
+  transpose_tile<T>(src + off, cols, rows, cols, dst + off, rows, rows, rt * 64, cti * 64);
+}
+
+// activations, kind 0: src [T*k, d] (expert e = rows offsets[e]..) -> dst [d, ldt], expert e at column poff[e]
+//              kind 1: src ragged [n_e, f_e] at hoff[e] -> dst [f_e, npad_e] at hpoff[e]
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_act_kernel(LayerDims L, int kind, const int32_t* __restrict__ counts,
+                                                            const int32_t* __restrict__ offsets,
+                                                            const T* __restrict__ src, T* __restrict__ dst) {
+  const int e = blockIdx.y;
+  const int n_e = counts[e], npad = pad_tokens(n_e);
+  const int cols = kind == 0 ? L.d : L.f[e];
+  const int ct = (cols + 63) / 64;
+  const int rt = blockIdx.x / ct, cti = blockIdx.x % ct;
+  if (rt * 64 >= npad) return;
+  size_t hoff = 0, hpoff = 0, poff = 0;
+  for (int q = 0; q < e; ++q) {
+    hoff += (size_t)counts[q] * L.f[q];
+    hpoff += (size_t)pad_tokens(counts[q]) * L.f[q];
+    poff += pad_tokens(counts[q]);
+  }
+  if (kind == 0)
+    transpose_tile<T>(src + (size_t)offsets[e] * L.d, L.d, n_e, cols, dst + poff, L.ldt, npad, rt * 64, cti * 64);
+  else
+    transpose_tile<T>(src + hoff, cols, n_e, cols, dst + hpoff, npad, npad, rt * 64, cti * 64);
+}
+
+int num_cus() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n = prop.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
+}
+
+template <int BM, int BN, int NB, int WM, int WN, int EPI>
+hipError_t run_bf16(const GemmPlan* plan, int accumulate, int save_pre, int64_t max_tiles, hipStream_t s) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int LDS = 2 * (BM + NB * BN) * 128;
+  auto kern = gg_bf16_kernel<BM, BN, NB, WM, WN, EPI>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int per_cu = LDS > 80 * 1024 ? 1 : 2;
+  int64_t grid = (int64_t)num_cus() * per_cu;
+  if (max_tiles < grid) grid = max_tiles;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), LDS, s, plan, accumulate, save_pre);
+  return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t run_f32(const GemmPlan* plan, int accumulate, int save_pre, int64_t max_tiles, hipStream_t s) {
+  int64_t grid = (int64_t)num_cus() * 8;
+  if (max_tiles < grid) grid = max_tiles;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL((gg_f32_kernel<EPI>), dim3((unsigned)grid), dim3(256), 0, s, plan, accumulate, save_pre);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+TileShape gemm_tile_shape(modse_dtype dt, int epilogue, int64_t T) {
+  (void)T;
+  if (dt == MODSE_F32) return {64, 64};
+  if (epilogue == EPI_SWIGLU) return {256, 128};
+  return {256, 256};
+}
+
+hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* plan, int accumulate, int save_pre,
+                               int64_t max_tiles, hipStream_t s) {
+  if (dt == MODSE_F32) {
+    switch (epilogue) {
+      case EPI_STORE: return run_f32<EPI_STORE>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_STORE_F32: return run_f32<EPI_STORE_F32>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_SWIGLU: return run_f32<EPI_SWIGLU>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_SWIGLU_BWD: return run_f32<EPI_SWIGLU_BWD>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_STORE_DUALK: return run_f32<EPI_STORE_DUALK>(plan, accumulate, save_pre, max_tiles, s);
+    }
+    return hipErrorInvalidValue;
+  }
+  switch (epilogue) {
+    case EPI_STORE: return run_bf16<256, 256, 1, 128, 128, EPI_STORE>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_STORE_F32:
+      return run_bf16<256, 256, 1, 128, 128, EPI_STORE_F32>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_SWIGLU: return run_bf16<256, 128, 2, 128, 64, EPI_SWIGLU>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_SWIGLU_BWD:
+      return run_bf16<256, 256, 1, 128, 128, EPI_SWIGLU_BWD>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_STORE_DUALK:
+      return run_bf16<256, 256, 1, 128, 128, EPI_STORE_DUALK>(plan, accumulate, save_pre, max_tiles, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
+                           const FwdPlanArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(plan_fwd_kernel, dim3(1), dim3(64), 0, s, L, dt == MODSE_F32 ? 4 : 2, counts, offsets, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan_bwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
+                           const BwdPlanArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(plan_bwd_kernel, dim3(1), dim3(64), 0, s, L, dt == MODSE_F32 ? 4 : 2, counts, offsets, a);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t transpose_weights_typed(const LayerDims& L, const T* W1, const T* W3, const T* W2, T* W1T, T* W3T,
+                                          T* W2T, hipStream_t s) {
+  int fmax = 0;
+  for (int e = 0; e < L.N; ++e) fmax = L.f[e] > fmax ? L.f[e] : fmax;
+  const unsigned gx = ((fmax + 63) / 64) * ((L.d + 63) / 64);
+  hipLaunchKernelGGL((transpose_weights_kernel<T>), dim3(gx, L.N), dim3(256), 0, s, L, 0, W1, W1T);
+  hipLaunchKernelGGL((transpose_weights_kernel<T>), dim3(gx, L.N), dim3(256), 0, s, L, 0, W3, W3T);
+  hipLaunchKernelGGL((transpose_weights_kernel<T>), dim3(gx, L.N), dim3(256), 0, s, L, 1, W2, W2T);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_weights(const LayerDims& L, modse_dtype dt, const void* W1, const void* W3,
+                                    const void* W2, void* W1T, void* W3T, void* W2T, hipStream_t s) {
+  if (dt == MODSE_F32)
+    return transpose_weights_typed<float>(L, (const float*)W1, (const float*)W3, (const float*)W2, (float*)W1T,
+                                          (float*)W3T, (float*)W2T, s);
+  return transpose_weights_typed<bf16_t>(L, (const bf16_t*)W1, (const bf16_t*)W3, (const bf16_t*)W2, (bf16_t*)W1T,
+                                         (bf16_t*)W3T, (bf16_t*)W2T, s);
+}
+
+hipError_t launch_transpose_act(const LayerDims& L, modse_dtype dt, int kind, const int32_t* counts,
+                                const int32_t* offsets, const void* src, void* dst, hipStream_t s) {
+  int fmax = 0;
+  for (int e = 0; e < L.N; ++e) fmax = L.f[e] > fmax ? L.f[e] : fmax;
+  const int cols = kind == 0 ? L.d : fmax;
+  const unsigned gx = ((L.T + 63) / 64 + 1) * ((cols + 63) / 64);
+  if (dt == MODSE_F32)
+    hipLaunchKernelGGL((transpose_act_kernel<float>), dim3(gx, L.N), dim3(256), 0, s, L, kind, counts, offsets,
+                       (const float*)src, (float*)dst);
+  else
+    hipLaunchKernelGGL((transpose_act_kernel<bf16_t>), dim3(gx, L.N), dim3(256), 0, s, L, kind, counts, offsets,
+                       (const bf16_t*)src, (bf16_t*)dst);
+  return hipGetLastError();
+}

@@ -1,0 +1,97 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every function that
+include/modse.h declares, and rejects bad arguments before touching the device."""
+import os
+import re
+
+import pytest
+
+import paper_2409_12210_amd as m
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+C0 = dict(d_model=256, d_ff=[128, 384, 192, 320, 224, 288, 256, 256], top_k=2, dtype="f32")
+OK, INVALID, UNSUPPORTED, WORKSPACE = 0, 1, 2, 3
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "modse.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(modse_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = m.load_library()
+    names = declared_functions()
+    assert {"modse_route", "modse_layer_fwd", "modse_layer_bwd", "modse_workspace_size"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_has_the_same_names():
+    for n in declared_functions():
+        assert hasattr(m, n), n
+
+
+def test_status_strings():
+    assert m.modse_status_string(0) == "ok"
+    assert "workspace" in m.modse_status_string(3)
+    assert m.modse_status_string(77) == "unknown status"
+
+
+def ws(T=512, bwd=False, **over):
+    a = dict(C0, **over)
+    return m.modse_workspace_size(a["d_model"], a["d_ff"], a["top_k"], a["dtype"], T, bwd, raise_on_error=False)
+
+
+def test_workspace_size_grows_with_tokens_and_backward():
+    a, b = ws(512), ws(1024)
+    assert 0 < a < b
+    assert ws(512, bwd=True) > a
+    assert ws(0) >= 0
+    assert m.modse_saved_size(256, C0["d_ff"], 2, "bf16", 512) > 0
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(d_model=250), INVALID),
+    (dict(d_ff=[128, 100]), INVALID),
+    (dict(d_ff=[128, 0]), INVALID),
+    (dict(d_ff=[128, -32]), INVALID),
+    (dict(top_k=0), INVALID),
+    (dict(top_k=9), INVALID),
+    (dict(top_k=3), UNSUPPORTED),
+    (dict(d_ff=[32] * 65), UNSUPPORTED),
+    (dict(dtype="fp8"), UNSUPPORTED),
+])
+def test_bad_descriptors(over, code):
+    assert ws(**over) == code
+
+
+def test_negative_tokens_and_huge_sizes():
+    assert ws(T=-1) == INVALID
+    assert ws(T=1 << 40) == UNSUPPORTED
+
+
+def test_calls_reject_null_pointers_and_small_workspace_before_any_launch():
+    a = (C0["d_model"], C0["d_ff"], C0["top_k"], C0["dtype"], 16)
+    assert m.modse_route(*a, None, None, None, None, None, stream=0, raise_on_error=False) == INVALID
+    fake = 0x1000      # never dereferenced: every check below fails first
+    r = m.Routing(fake, fake, fake, fake, fake, fake, fake)
+    assert m.modse_route(*a, fake, fake, None, r, fake, ws_bytes=16, stream=0, raise_on_error=False) == WORKSPACE
+    assert m.modse_layer_fwd(*a, fake, fake, None, fake, fake, fake, fake, None, None, fake, ws_bytes=16, stream=0,
+                             raise_on_error=False) == WORKSPACE
+    assert m.modse_layer_fwd(*a, fake, fake, None, fake, None, fake, fake, None, None, fake, ws_bytes=1 << 30,
+                             stream=0, raise_on_error=False) == INVALID
+    r_bad = m.Routing(fake, fake, fake, None, fake, fake, fake)
+    assert m.modse_layer_fwd(*a, fake, fake, None, fake, fake, fake, fake, r_bad, None, fake, ws_bytes=1 << 30,
+                             stream=0, raise_on_error=False) == INVALID
+    assert m.modse_layer_bwd(*a, fake, fake, fake, fake, fake, r, fake, fake, fake, fake, fake, fake, fake, 0, fake,
+                             ws_bytes=16, stream=0, raise_on_error=False) == WORKSPACE
+    assert m.modse_layer_bwd(*a, fake, fake, fake, fake, fake, r, None, fake, fake, fake, fake, fake, fake, 0, fake,
+                             ws_bytes=1 << 30, stream=0, raise_on_error=False) == INVALID
+    with pytest.raises(m.ModseError):
+        m.modse_route(*a, None, None, None, None, None, stream=0)
+
+
+def test_zero_tokens_is_a_noop():
+    a = (C0["d_model"], C0["d_ff"], C0["top_k"], C0["dtype"], 0)
+    assert m.modse_layer_fwd(*a, None, None, None, None, None, None, None, None, None, None, ws_bytes=0, stream=0,
+                             raise_on_error=False) == OK
