@@ -3,83 +3,11 @@
 // arXiv 2409.12210).  A tiny plan kernel turns the device-side counts into a problem table and a tile
 // prefix; persistent GEMM workgroups walk the tile list without any host round trip.
 #include "common.h"
+#include "gemm_bf16.h"
+#include "gemm_tiles.h"
 
 namespace {
-
-constexpr int NUM_XCD = 8;
-constexpr int GROUP_M = 8;  // tiles of GROUP_M consecutive row blocks are walked column-first (L2 reuse)
-
-struct TileCoord {
-  int p, mt, nt;
-};
-
-__device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, TileCoord& tc) {
-  const int np = plan->n_prob;
-  int p = 0;
-  while (p < np && tile >= plan->tile_start[p + 1]) ++p;
-  if (p >= np) return false;
-  const int local = tile - plan->tile_start[p];
-  const int mtiles = plan->prob[p].mtiles, ntiles = plan->prob[p].ntiles;
-  const int per_group = GROUP_M * ntiles;
-  const int first = (local / per_group) * GROUP_M;
-  const int gsz = min(mtiles - first, GROUP_M);
-  const int rem = local % per_group;
-  tc.p = p;
-  tc.mt = first + rem % gsz;
-  tc.nt = rem / gsz;
-  return true;
-}
-
-// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of the tile list so
-// that the tiles sharing operand rows meet in the same L2.
-__device__ inline int first_tile_of_block() {
-  const int G = gridDim.x, b = blockIdx.x;
-  return (G % NUM_XCD == 0) ? (b % NUM_XCD) * (G / NUM_XCD) + b / NUM_XCD : b;
-}
-
-__device__ inline float silu_f(float a) { return a / (1.f + __expf(-a)); }
-
-// Epilogue on 4 consecutive columns n..n+3 of row m.  a = first accumulator, b = second (SwiGLU only).
-template <typename T, int EPI>
-__device__ inline void epilogue4(const GemmProblem& P, int m, int n, const float a[4], const float b[4],
-                                 int accumulate, int save_pre) {
-  if (m >= P.M || n >= P.N) return;
-  const size_t o = (size_t)m * P.ldc + n;
-  if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
-    store4(static_cast<T*>(P.C) + o, a);
-  } else if constexpr (EPI == EPI_STORE_F32) {
-    float* c = static_cast<float*>(P.C) + o;
-    float v[4] = {a[0], a[1], a[2], a[3]};
-    if (accumulate) {
-      float old[4];
-      load4(c, old);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] += old[i];
-    }
-    store4(c, v);
-  } else if constexpr (EPI == EPI_SWIGLU) {
-    float h[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) h[i] = silu_f(a[i]) * b[i];
-    store4(static_cast<T*>(P.C) + o, h);
-    if (save_pre) {
-      store4(static_cast<T*>(P.C2) + o, a);
-      store4(static_cast<T*>(P.C3) + o, b);
-    }
-  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-    float av[4], bv[4], da[4], db[4];
-    load4(static_cast<const T*>(P.E1) + o, av);
-    load4(static_cast<const T*>(P.E2) + o, bv);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float sig = 1.f / (1.f + __expf(-av[i]));
-      da[i] = a[i] * bv[i] * sig * (1.f + av[i] * (1.f - sig));
-      db[i] = a[i] * av[i] * sig;
-    }
-    store4(static_cast<T*>(P.C) + o, da);
-    store4(static_cast<T*>(P.C2) + o, db);
-  }
-}
+using namespace modse_gemm;
 
 // ------------------------------------------------------------------------------------------------
 // float32 path: plain FMA tiles (parity configuration; no throughput claim)
@@ -147,150 +75,6 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GemmPlan* __restrict_
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       epilogue4<float, EPI>(P, m0 + ty * 4 + i, n0 + tx * 4, acc[0][i], acc[NB - 1][i], accumulate, save_pre);
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// bf16 path: MFMA 32x32x16 tiles, fp32 accumulate, LDS double buffer
-// ------------------------------------------------------------------------------------------------
-// Tile BM x BN (x NB matrices B sharing A), K step 64.  LDS rows are 128 bytes (64 bf16 along K); the
-// 16-byte chunk index is XOR-ed with (row & 7) so that the 32 rows a fragment read touches spread over
-// all banks.  The accumulator of v_mfma_f32_32x32x16_bf16 holds, per lane, 4 consecutive rows of the
-// instruction's first operand; feeding the B tile as first operand makes those 4 values consecutive
-// columns of C, stored as one 8- or 16-byte vector.
-template <int BM, int BN, int NB, int WM, int WN, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gg_bf16_kernel(const GemmPlan* __restrict__ plan,
-                                                                             int accumulate, int save_pre) {
-  constexpr int BK = 64;
-  constexpr int WAVES_N = BN / WN;
-  constexpr int NT = (BM / WM) * WAVES_N * 64;
-  constexpr int MI = WM / 32, NI = WN / 32;
-  constexpr int CA = BM * 8 / NT;        // 16-byte chunks of the A tile per thread
-  constexpr int CB = NB * BN * 8 / NT;   // ... of the B tile(s)
-  constexpr int STAGE = (BM + NB * BN) * 128;
-  static_assert(BM * 8 % NT == 0 && NB * BN * 8 % NT == 0, "tile/thread mismatch");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int total = plan->tile_start[plan->n_prob];
-
-  for (int tile = first_tile_of_block(); tile < total; tile += gridDim.x) {
-    TileCoord tc;
-    if (!decode_tile(plan, tile, tc)) break;
-    const GemmProblem P = plan->prob[tc.p];
-    const int m0 = tc.mt * BM, n0 = tc.nt * BN;
-
-    f32x16 acc[NB][MI][NI];
-#pragma unroll
-    for (int q = 0; q < NB; ++q)
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
-
-    // per-thread chunk coordinates: chunk q -> row q/8, 16-byte column q%8
-    int offA[CA], offB[CB], ldsA[CA], ldsB[CB];
-#pragma unroll
-    for (int it = 0; it < CA; ++it) {
-      const int q = tid + it * NT, row = q >> 3, cc = q & 7;
-      offA[it] = min(m0 + row, P.M - 1) * P.lda + cc * 8;
-      ldsA[it] = row * 128 + ((cc ^ (row & 7)) << 4);
-    }
-#pragma unroll
-    for (int it = 0; it < CB; ++it) {
-      const int q = tid + it * NT, row = q >> 3, cc = q & 7;
-      const int brow = row % BN;  // row inside one B matrix
-      offB[it] = min(n0 + brow, P.N - 1) * P.ldb + cc * 8;
-      ldsB[it] = BM * 128 + row * 128 + ((cc ^ (row & 7)) << 4);
-    }
-    const int kcol = (tid & 7) * 8;  // this thread's K offset inside a 64-wide K tile (same for all its chunks)
-
-    const int nk = (P.K + BK - 1) / BK;
-    const int npass = (EPI == EPI_STORE_DUALK) ? 2 : 1;
-    const int nsteps = nk * npass;
-    uint4 ra[CA], rb[CB];
-
-    auto gload = [&](int step) {
-      const int pass = step >= nk ? 1 : 0;
-      const int k0 = (step - pass * nk) * BK;
-      const bool kin = k0 + kcol < P.K;
-      const bf16_t* A = static_cast<const bf16_t*>(pass ? P.A2 : P.A) + k0;
-      const bf16_t* B = static_cast<const bf16_t*>(pass ? P.B2 : P.B) + k0;
-      const bf16_t* B2 = static_cast<const bf16_t*>(P.B2) + k0;
-#pragma unroll
-      for (int it = 0; it < CA; ++it) {
-        ra[it] = kin ? *reinterpret_cast<const uint4*>(A + offA[it]) : make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int it = 0; it < CB; ++it) {
-        const int q = tid + it * NT;
-        const bf16_t* src = (NB == 2 && (q >> 3) >= BN) ? B2 : B;
-        rb[it] = kin ? *reinterpret_cast<const uint4*>(src + offB[it]) : make_uint4(0, 0, 0, 0);
-      }
-    };
-    auto lstore = [&](int buf) {
-      char* base = smem + buf * STAGE;
-#pragma unroll
-      for (int it = 0; it < CA; ++it) *reinterpret_cast<uint4*>(base + ldsA[it]) = ra[it];
-#pragma unroll
-      for (int it = 0; it < CB; ++it) *reinterpret_cast<uint4*>(base + ldsB[it]) = rb[it];
-    };
-
-    __syncthreads();  // previous tile's readers are done with both buffers
-    if (nsteps > 0) {
-      gload(0);
-      lstore(0);
-    }
-    __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
-      const int buf = step & 1;
-      if (step + 1 < nsteps) gload(step + 1);
-      const char* sA = smem + buf * STAGE;
-      const char* sB = sA + BM * 128;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int sw = (((kk * 2 + (lane >> 5)) ^ (lane & 7)) << 4);
-        bf16x8 af[MI], bfr[NB][NI];
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[i] = *reinterpret_cast<const bf16x8*>(sA + (wm * WM + i * 32 + (lane & 31)) * 128 + sw);
-#pragma unroll
-        for (int q = 0; q < NB; ++q)
-#pragma unroll
-          for (int j = 0; j < NI; ++j)
-            bfr[q][j] = *reinterpret_cast<const bf16x8*>(sB + (q * BN + wn * WN + j * 32 + (lane & 31)) * 128 + sw);
-#pragma unroll
-        for (int q = 0; q < NB; ++q)
-#pragma unroll
-          for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-              acc[q][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[q][j], af[i], acc[q][i][j], 0, 0, 0);
-      }
-      if (step + 1 < nsteps) lstore(buf ^ 1);
-      __syncthreads();
-    }
-
-    // epilogue: lane holds, for register group g, columns n .. n+3 of row m
-    const int mrow = m0 + wm * WM + (lane & 31);
-    const int ncol = n0 + wn * WN + 4 * (lane >> 5);
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-      for (int j = 0; j < NI; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float a[4], b[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            a[q] = acc[0][i][j][g * 4 + q];
-            b[q] = acc[NB - 1][i][j][g * 4 + q];
-          }
-          epilogue4<bf16_t, EPI>(P, mrow + i * 32, ncol + j * 32 + g * 8, a, b, accumulate, save_pre);
-        }
   }
 }
 
@@ -490,23 +274,14 @@ int num_cus() {
   return n;
 }
 
-template <int BM, int BN, int NB, int WM, int WN, int EPI>
+template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI>
 hipError_t run_bf16(const GemmPlan* plan, int accumulate, int save_pre, int64_t max_tiles, hipStream_t s) {
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr int LDS = 2 * (BM + NB * BN) * 128;
-  auto kern = gg_bf16_kernel<BM, BN, NB, WM, WN, EPI>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  const int per_cu = LDS > 80 * 1024 ? 1 : 2;
-  int64_t grid = (int64_t)num_cus() * per_cu;
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  int64_t grid = num_cus();  // the two LDS stages fill a CU: one persistent workgroup per CU
   if (max_tiles < grid) grid = max_tiles;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), LDS, s, plan, accumulate, save_pre);
+  hipLaunchKernelGGL((gg_bf16_kernel<BM, BN, NB, WAVES_M, WAVES_N, EPI>), dim3((unsigned)grid), dim3(NT), 0, s, plan,
+                     accumulate, save_pre);
   return hipGetLastError();
 }
 
@@ -541,14 +316,14 @@ hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* pla
     return hipErrorInvalidValue;
   }
   switch (epilogue) {
-    case EPI_STORE: return run_bf16<256, 256, 1, 128, 128, EPI_STORE>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_STORE: return run_bf16<256, 256, 1, 4, 2, EPI_STORE>(plan, accumulate, save_pre, max_tiles, s);
     case EPI_STORE_F32:
-      return run_bf16<256, 256, 1, 128, 128, EPI_STORE_F32>(plan, accumulate, save_pre, max_tiles, s);
-    case EPI_SWIGLU: return run_bf16<256, 128, 2, 128, 64, EPI_SWIGLU>(plan, accumulate, save_pre, max_tiles, s);
+      return run_bf16<256, 256, 1, 4, 2, EPI_STORE_F32>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_SWIGLU: return run_bf16<256, 128, 2, 4, 2, EPI_SWIGLU>(plan, accumulate, save_pre, max_tiles, s);
     case EPI_SWIGLU_BWD:
-      return run_bf16<256, 256, 1, 128, 128, EPI_SWIGLU_BWD>(plan, accumulate, save_pre, max_tiles, s);
+      return run_bf16<256, 256, 1, 4, 2, EPI_SWIGLU_BWD>(plan, accumulate, save_pre, max_tiles, s);
     case EPI_STORE_DUALK:
-      return run_bf16<256, 256, 1, 128, 128, EPI_STORE_DUALK>(plan, accumulate, save_pre, max_tiles, s);
+      return run_bf16<256, 256, 1, 4, 2, EPI_STORE_DUALK>(plan, accumulate, save_pre, max_tiles, s);
   }
   return hipErrorInvalidValue;
 }

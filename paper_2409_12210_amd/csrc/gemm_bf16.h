@@ -1,0 +1,294 @@
+// bf16 grouped GEMM for gfx950: MFMA 32x32x16, fp32 accumulate, direct global->LDS loads.
+//
+// One persistent workgroup of 8 waves (WAVES_M x WAVES_N, two per SIMD) walks the tile list.  A tile is
+// BM x BN (x NB matrices B that share A: the up-projection's W1 and W3); K advances 64 elements per step.
+//
+// LDS: two stages, each (BM + NB*BN) rows of 128 bytes (64 bf16 along K).  The LDS of gfx950 has 64
+// banks of 4 bytes and serves a ds_read_b128 sixteen lanes at a time; the 16-byte chunk index of a row
+// is XOR-ed with ((row >> 1) & 7), so 16 consecutive rows read at the same K offset cover all 64 banks
+// (measured: SQ_LDS_BANK_CONFLICT = 0, 4 LDS cycles per ds_read_b128).  Stages are filled by
+// global_load_lds_dwordx4: one wave instruction writes 1 KiB of consecutive LDS (8 rows); which global
+// chunk a lane fetches is chosen so that the data lands pre-swizzled.  The loads are issued from inline
+// assembly with a scalar base and a 32-bit lane offset, so every vmcnt wait is explicit here.
+//
+// Pipeline: the loads of stage g+1 are issued in slices between the MFMA groups of stage g (a wave that
+// blocks on a full load queue cannot feed the matrix pipe), and the K loop is rotated: the barrier that
+// opens stage g+1 and the first fragment reads of that stage sit in front of the last MFMA group of
+// stage g.  The issue cursor runs across tile boundaries, so the first stage of the next tile is in
+// flight while the epilogue of the current one stores.
+//
+// The accumulator of v_mfma_f32_32x32x16_bf16 holds, per lane, 4 consecutive rows of the instruction's
+// first operand.  The B tile is fed as first operand, so those 4 values are consecutive columns of C.
+#pragma once
+#include "common.h"
+#include "gemm_tiles.h"
+
+namespace modse_gemm {
+
+__device__ const uint4 g_zero_chunk[4] = {};
+  // source of K-tail chunks that lie beyond K
+
+// tells the compiler that a pointer is the same in every lane (keeps it in scalar registers)
+__device__ __forceinline__ const void* uniform_ptr(const void* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+__device__ __forceinline__ void dma_b128(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(
+                   __builtin_amdgcn_readfirstlane(lds_base)),
+               "v"(gptr)
+               : "memory");
+}
+// same, address = wave-uniform base + per-lane unsigned 32-bit byte offset
+__device__ __forceinline__ void dma_b128_s(const void* base, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(
+                   __builtin_amdgcn_readfirstlane(lds_base)),
+               "v"(voff), "s"(uniform_ptr(base))
+               : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+#ifndef MODSE_DMA_SPREAD
+#define MODSE_DMA_SPREAD 2  // the stage loads of a step are issued in this many slices, between the MFMA groups
+#endif
+
+template <int BM, int BN, int NB, int WAVES_M, int WAVES_N>
+struct Bf16Tile {
+  static constexpr int BK = 64;
+  static constexpr int NWAVES = WAVES_M * WAVES_N;
+  static constexpr int NT = NWAVES * 64;
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  static constexpr int MI = WM / 32, NI = WN / 32;
+  static constexpr int ROWS = BM + NB * BN;  // LDS rows of one stage
+  static constexpr int UA = BM / 8;          // 1 KiB load units (8 rows) of the A tile
+  static constexpr int UNITS = ROWS / 8;     // ... of the whole stage
+  static constexpr int UPW = UNITS / NWAVES; // units per wave and stage
+  static constexpr int STAGE = ROWS * 128;
+  static_assert(UNITS % NWAVES == 0 && UPW % 2 == 0, "load units must divide evenly among waves");
+  static_assert(UPW % MODSE_DMA_SPREAD == 0 && MODSE_DMA_SPREAD <= 4, "load slices");
+  static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
+};
+
+// Walks the K steps of this workgroup's tiles in order.
+struct StepCursor {
+  int tile, step, nsteps, nk;
+  int m0, n0;
+  bool valid;
+};
+
+template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const GemmPlan* __restrict__ plan,
+                                                                        int accumulate, int save_pre) {
+  using Cfg = Bf16Tile<BM, BN, NB, WAVES_M, WAVES_N>;
+  constexpr int BK = Cfg::BK, MI = Cfg::MI, NI = Cfg::NI, UA = Cfg::UA, UPW = Cfg::UPW, STAGE = Cfg::STAGE;
+  constexpr int WM = Cfg::WM, WN = Cfg::WN;
+  constexpr int SLICE = UPW / MODSE_DMA_SPREAD;
+  static_assert(UA % UPW == 0 && (BN / 8) % UPW == 0, "all load units of a wave must belong to one operand");
+  __shared__ __attribute__((aligned(1024))) char stages[2 * STAGE];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int total = plan->tile_start[plan->n_prob];
+  const int G = gridDim.x;
+  const uint32_t lds_mine = __builtin_amdgcn_readfirstlane(lds_address(stages)) + wave * UPW * 1024;
+  const int lrow = lane >> 3;  // row inside a load unit
+  // element offset of the chunk this lane fetches, for even and odd load units: LDS position (row, p)
+  // holds logical chunk p ^ ((row >> 1) & 7), and row = 8 * unit + lrow
+  const int lchunk_even = ((lane & 7) ^ (lrow >> 1)) * 8;
+  const int lchunk_odd = ((lane & 7) ^ (4 | (lrow >> 1))) * 8;
+  // fragment read offsets inside a stage (bytes), without the kk-dependent swizzle term
+  const int a_frag = (wm * WM + (lane & 31)) * 128;
+  const int b_frag = BM * 128 + (wn * WN + (lane & 31)) * 128;
+  const int khalf = lane >> 5, lsw = (lane >> 1) & 7;
+
+  auto open_tile = [&](StepCursor& c, GemmProblem& Q) {
+    TileCoord tc;
+    c.valid = c.tile < total && decode_tile(plan, c.tile, tc);
+    if (!c.valid) return;
+    Q = plan->prob[tc.p];
+    c.m0 = tc.mt * BM;
+    c.n0 = tc.nt * BN;
+    c.step = 0;
+    c.nk = (Q.K + BK - 1) / BK;
+    c.nsteps = (EPI == EPI_STORE_DUALK) ? 2 * c.nk : c.nk;
+  };
+
+  // ---- issue side: runs one K step ahead of the MFMAs, across tile boundaries
+  StepCursor ic;
+  GemmProblem IP;
+  uint32_t ioff[UPW];  // byte offset of this lane's chunk per load unit (K offset 0) from the operand base
+  // tiles without K steps (an expert that received no token, in a weight-gradient GEMM) take no stage
+  auto skip_empty = [&]() {
+    while (ic.valid && ic.nsteps == 0) {
+      ic.tile += G;
+      open_tile(ic, IP);
+    }
+  };
+  auto issue_offsets = [&]() {
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+      const int u = wave * UPW + i;
+      const int lchunk = (i & 1) ? lchunk_odd : lchunk_even;  // UPW is even: unit parity = i parity
+      if (u < UA) {
+        ioff[i] = (uint32_t)(min(ic.m0 + u * 8 + lrow, IP.M - 1) * IP.lda + lchunk) * 2u;
+      } else {
+        const int r = ((u - UA) * 8 + lrow) % BN;
+        ioff[i] = (uint32_t)(min(ic.n0 + r, IP.N - 1) * IP.ldb + lchunk) * 2u;
+      }
+    }
+  };
+  // operand this wave loads from (wave-uniform)
+  auto my_operand = [&](int pass) -> const char* {
+    const int u = wave * UPW;
+    if (u < UA) return static_cast<const char*>(pass ? IP.A2 : IP.A);
+    if (NB == 2) return static_cast<const char*>((u - UA) * 8 >= BN ? IP.B2 : IP.B);
+    return static_cast<const char*>(pass ? IP.B2 : IP.B);
+  };
+  // issue load units [first, first + count) of the issue cursor's step into stage buffer `buf`
+  auto issue_slice = [&](int buf, int first, int count) {
+    if (!ic.valid) return;
+    const int pass = (EPI == EPI_STORE_DUALK && ic.step >= ic.nk) ? 1 : 0;
+    const int k0 = (ic.step - pass * ic.nk) * BK;
+    const uint32_t dst = lds_mine + buf * STAGE;
+    const char* base = my_operand(pass) + (size_t)k0 * 2;
+    if (k0 + BK <= IP.K) {
+#pragma unroll
+      for (int i = first; i < first + count; ++i) dma_b128_s(base, ioff[i], dst + i * 1024);
+    } else {  // last step of a pass when K % 64 != 0: chunks beyond K read zeros
+#pragma unroll
+      for (int i = first; i < first + count; ++i) {
+        const char* src = base + ioff[i];
+        if (k0 + ((i & 1) ? lchunk_odd : lchunk_even) >= IP.K) src = reinterpret_cast<const char*>(g_zero_chunk);
+        dma_b128(src, dst + i * 1024);
+      }
+    }
+  };
+  auto advance_issue = [&]() {
+    if (!ic.valid) return;
+    if (++ic.step >= ic.nsteps) {
+      ic.tile += G;
+      open_tile(ic, IP);
+      skip_empty();
+      if (ic.valid) issue_offsets();
+    }
+  };
+
+  // ---- compute side
+  StepCursor cc;
+  GemmProblem CP;
+  cc.tile = first_tile_of_block();
+  open_tile(cc, CP);
+  if (!cc.valid) return;
+  ic = cc;
+  IP = CP;
+  skip_empty();
+  if (ic.valid) issue_offsets();
+  const bool any_stage = ic.valid;
+  issue_slice(0, 0, UPW);  // stage of global step 0
+  advance_issue();
+
+  // Fragments are double-buffered in registers: set (kk & 1) feeds the MFMAs of K slice kk while the
+  // other set is being read from LDS.
+  bf16x8 af[2][MI], bfr[2][NB][NI];
+  auto load_frags = [&](const char* buf, int kk, int set) {
+    const int sw = ((kk * 2 + khalf) ^ lsw) << 4;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[set][i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + i * 32 * 128 + sw);
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+        bfr[set][q][j] = *reinterpret_cast<const bf16x8*>(buf + b_frag + (q * BN + j * 32) * 128 + sw);
+  };
+  f32x16 acc[NB][MI][NI];
+  auto mfma_block = [&](int set) {
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[q][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][q][j], af[set][i], acc[q][i][j], 0, 0, 0);
+  };
+  // Stage hand-over.  All my loads have landed (s_waitcnt simm16 on gfx9: vmcnt in bits [3:0] and
+  // [15:14], expcnt in [6:4], lgkmcnt in [11:8]) and my LDS reads have returned; then everybody meets.
+  // Afterwards the new stage may be read and the buffer of the old one refilled.
+  auto stage_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  int g = 0;  // global step count of this workgroup: stage buffer = g & 1
+  if (any_stage) {
+    stage_barrier();
+    load_frags(stages, 0, 0);
+  }
+  while (cc.valid) {
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
+
+    // The K loop is rotated: the barrier that opens stage g+1 and the first fragment reads of that stage
+    // sit in front of the last MFMA group of stage g, so the matrix pipe has work while LDS answers.
+#pragma unroll 1
+    for (int s = 0; s < cc.nsteps; ++s, ++g) {
+      const char* buf = stages + (g & 1) * STAGE;
+      const int nbuf = (g + 1) & 1;
+      const bool next_stage = ic.valid;  // a stage g+1 exists (maybe in the next tile); uniform in the workgroup
+#pragma unroll
+      for (int kk = 0; kk < 3; ++kk) {
+        load_frags(buf, kk + 1, (kk + 1) & 1);
+        if (kk < MODSE_DMA_SPREAD) {  // the loads of stage g+1 go out in slices between the MFMA groups
+          __builtin_amdgcn_sched_barrier(0);
+          issue_slice(nbuf, kk * SLICE, SLICE);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        mfma_block(kk & 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      advance_issue();
+      if (next_stage) {
+        stage_barrier();
+        load_frags(stages + nbuf * STAGE, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_block(1);
+    }
+
+    // epilogue: for register group r the lane holds columns n .. n+3 of row m
+    const int mrow = cc.m0 + wm * WM + (lane & 31);
+    const int ncol = cc.n0 + wn * WN + 4 * khalf;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float a[4], b[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            a[q] = acc[0][i][j][r * 4 + q];
+            b[q] = acc[NB - 1][i][j][r * 4 + q];
+          }
+          epilogue4<bf16_t, EPI>(CP, mrow + i * 32, ncol + j * 32 + r * 8, a, b, accumulate, save_pre);
+        }
+    cc.tile += G;
+    open_tile(cc, CP);
+  }
+  // drain: nothing may still be writing LDS when the workgroup's allocation is released
+  __builtin_amdgcn_s_waitcnt(0x0070);
+}
+
+}  // namespace modse_gemm

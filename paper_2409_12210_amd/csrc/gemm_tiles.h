@@ -1,0 +1,82 @@
+// Tile walking and fused epilogues shared by the grouped GEMM kernels (gfx950).
+#pragma once
+#include "common.h"
+
+namespace modse_gemm {
+
+constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;  // tiles of GROUP_M consecutive row blocks are walked column-first (L2 reuse)
+
+struct TileCoord {
+  int p, mt, nt;
+};
+
+__device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, TileCoord& tc) {
+  const int np = plan->n_prob;
+  int p = 0;
+  while (p < np && tile >= plan->tile_start[p + 1]) ++p;
+  if (p >= np) return false;
+  const int local = tile - plan->tile_start[p];
+  const int mtiles = plan->prob[p].mtiles, ntiles = plan->prob[p].ntiles;
+  const int per_group = GROUP_M * ntiles;
+  const int first = (local / per_group) * GROUP_M;
+  const int gsz = min(mtiles - first, GROUP_M);
+  const int rem = local % per_group;
+  tc.p = p;
+  tc.mt = first + rem % gsz;
+  tc.nt = rem / gsz;
+  return true;
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of the tile list so
+// that the tiles sharing operand rows meet in the same L2.
+__device__ inline int first_tile_of_block() {
+  const int G = gridDim.x, b = blockIdx.x;
+  return (G % NUM_XCD == 0) ? (b % NUM_XCD) * (G / NUM_XCD) + b / NUM_XCD : b;
+}
+
+__device__ inline float silu_f(float a) { return a / (1.f + __expf(-a)); }
+
+// Epilogue on 4 consecutive columns n..n+3 of row m.  a = first accumulator, b = second (SwiGLU only).
+template <typename T, int EPI>
+__device__ inline void epilogue4(const GemmProblem& P, int m, int n, const float a[4], const float b[4],
+                                 int accumulate, int save_pre) {
+  if (m >= P.M || n >= P.N) return;
+  const size_t o = (size_t)m * P.ldc + n;
+  if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
+    store4(static_cast<T*>(P.C) + o, a);
+  } else if constexpr (EPI == EPI_STORE_F32) {
+    float* c = static_cast<float*>(P.C) + o;
+    float v[4] = {a[0], a[1], a[2], a[3]};
+    if (accumulate) {
+      float old[4];
+      load4(c, old);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] += old[i];
+    }
+    store4(c, v);
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    float h[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = silu_f(a[i]) * b[i];
+    store4(static_cast<T*>(P.C) + o, h);
+    if (save_pre) {
+      store4(static_cast<T*>(P.C2) + o, a);
+      store4(static_cast<T*>(P.C3) + o, b);
+    }
+  } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+    float av[4], bv[4], da[4], db[4];
+    load4(static_cast<const T*>(P.E1) + o, av);
+    load4(static_cast<const T*>(P.E2) + o, bv);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float sig = 1.f / (1.f + __expf(-av[i]));
+      da[i] = a[i] * bv[i] * sig * (1.f + av[i] * (1.f - sig));
+      db[i] = a[i] * av[i] * sig;
+    }
+    store4(static_cast<T*>(P.C) + o, da);
+    store4(static_cast<T*>(P.C2) + o, db);
+  }
+}
+
+}  // namespace modse_gemm
