@@ -28,6 +28,19 @@ def realised_flops(counts, d_ff, d):
     return 4.0 * d * s, 2.0 * d * s
 
 
+def measured_traffic(cfg_name, mode):
+    """HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
+    kept under profiles/ (a line 'hbm_bytes_per_launch: N'); None if no summary covers this workload."""
+    path = os.path.join(ROOT, "profiles", f"gg_bf16_swiglu_{cfg_name}_{mode}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("hbm_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg_name, mode, sample_tokens):
     """Times the CPU oracle, as it stands, on the first `sample_tokens` tokens of the same workload."""
     import numpy as np
@@ -58,7 +71,9 @@ def main():
     ap.add_argument("--config", default="C1")
     ap.add_argument("--mode", default="fwd_bwd", choices=["fwd_bwd", "fwd"])
     ap.add_argument("--tokens", type=int, default=0, help="override the token count of the config")
-    ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens for the CPU-oracle baseline (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens for the CPU-oracle baseline (0 = skip)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path is single-GPU; see DESIGN.md for how it "
@@ -93,6 +108,15 @@ def main():
         if bwd:
             r.bwd()
 
+    if args.calib_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read + 1 GiB written per copy
+        b = torch.empty_like(a)
+        a.fill_(1.0)
+        for _ in range(3):
+            torch.add(a, 1.0, out=b)   # an elementwise kernel with a recognisable name (not a DMA copy)
+        torch.cuda.synchronize()
+        del a, b
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -122,7 +146,7 @@ def main():
     up_tflops = up_flops / (stages["up"] * 1e-3) / 1e12 if stages["up"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": "gg_bf16_kernel<EPI_SWIGLU> (grouped W1/W3 GEMM + SwiGLU)",
                 "achieved": round(up_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(up_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(up_tflops / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.config, args.mode),
                 "flops_per_launch": up_flops, "avg_launch_ms": round(stages["up"], 4)}
     extra = {"fwd_grouped_gemm_tflops": round(fwd_gemm_tflops, 2),
              "fwd_grouped_gemm_frac_of_bf16_peak": round(fwd_gemm_tflops / PEAK_BF16_TFLOPS, 4),

@@ -23,10 +23,20 @@ __device__ inline double shfl_xor_f64(double v, int mask) {
 // the partner lane and keeps the other half, so V values cost V-1 + (6 - log2 V) shuffles.  On return
 // lane l (l < V) holds in vals[0] the total of value index bitrev_{log2 V}(l).
 template <int V>
-__device__ inline void wave_sum_values(double* vals, int lane) {
-  int bit = 1;
+struct Log2 {
+  static constexpr int value = 1 + Log2<V / 2>::value;
+};
+template <>
+struct Log2<1> {
+  static constexpr int value = 0;
+};
+
+template <int V>
+__device__ inline void wave_sum_values(double (&vals)[V], int lane) {
+  constexpr int P = Log2<V>::value;
 #pragma unroll
-  for (int width = V / 2; width >= 1; width /= 2) {
+  for (int s = 0; s < P; ++s) {
+    const int width = V >> (s + 1), bit = 1 << s;
     const bool upper = (lane & bit) != 0;
 #pragma unroll
     for (int i = 0; i < width; ++i) {
@@ -34,9 +44,9 @@ __device__ inline void wave_sum_values(double* vals, int lane) {
       const double send = upper ? vals[i] : vals[i + width];
       vals[i] = keep + shfl_xor_f64(send, bit);
     }
-    bit <<= 1;
   }
-  for (; bit < 64; bit <<= 1) vals[0] += shfl_xor_f64(vals[0], bit);
+#pragma unroll
+  for (int s = P; s < 6; ++s) vals[0] += shfl_xor_f64(vals[0], 1 << s);
 }
 
 template <int P>
@@ -46,15 +56,6 @@ __device__ inline int bitrev(int v) {
   for (int i = 0; i < P; ++i) r |= ((v >> i) & 1) << (P - 1 - i);
   return r;
 }
-
-template <int V>
-struct Log2 {
-  static constexpr int value = 1 + Log2<V / 2>::value;
-};
-template <>
-struct Log2<1> {
-  static constexpr int value = 0;
-};
 
 // One block routes TPB consecutive tokens.  blockhist[b][0..N-1] = this block's per-expert assignment
 // counts, blockhist[b][N] = its near-tie token count.
@@ -78,25 +79,25 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.0;
     for (int c = lane * 8; c < d; c += 64 * 8) {
-      float w[8][NE];
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int e = 0; e < NE; ++e) w[i][e] = (e < N) ? (float)Wg[(size_t)(c + i) * N + e] : 0.f;
+      float xv[TOK][8];
 #pragma unroll
       for (int tt = 0; tt < TOK; ++tt) {
-        const int t = tbase + tt;
-        float xv[8];
-        if (t < ntok) {
-          load8(x + (size_t)t * d + c, xv);
-        } else {
+        const int t = min(tbase + tt, ntok - 1);  // rows past the end repeat the last token; never written
+        load8(x + (size_t)t * d + c, xv[tt]);
+      }
 #pragma unroll
-          for (int i = 0; i < 8; ++i) xv[i] = 0.f;
+      for (int i = 0; i < 8; ++i) {  // one W_gate row at a time keeps the register footprint small
+        double w[NE];
+        const T* wrow = Wg + (size_t)(c + i) * N;
+        // columns e >= N repeat the last expert; their sums are never looked at
+#pragma unroll
+        for (int e = 0; e < NE; ++e) w[e] = (double)(float)wrow[min(e, N - 1)];
+#pragma unroll
+        for (int tt = 0; tt < TOK; ++tt) {
+          const double xd = (double)xv[tt][i];
+#pragma unroll
+          for (int e = 0; e < NE; ++e) acc[tt * NE + e] = fma(xd, w[e], acc[tt * NE + e]);
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int e = 0; e < NE; ++e) acc[tt * NE + e] = fma((double)xv[i], (double)w[i][e], acc[tt * NE + e]);
       }
     }
     wave_sum_values<V>(acc, lane);
@@ -431,8 +432,8 @@ hipError_t route_typed(const LayerDims& L, const void* xv, const void* Wgv, cons
   hipError_t e;
   if (L.N <= 2) e = run_router<T, 2, 4>(L, x, Wg, bias, R, blockhist, s);
   else if (L.N <= 4) e = run_router<T, 4, 4>(L, x, Wg, bias, R, blockhist, s);
-  else if (L.N <= 8) e = run_router<T, 8, 4>(L, x, Wg, bias, R, blockhist, s);
-  else if (L.N <= 16) e = run_router<T, 16, 2>(L, x, Wg, bias, R, blockhist, s);
+  else if (L.N <= 8) e = run_router<T, 8, 2>(L, x, Wg, bias, R, blockhist, s);
+  else if (L.N <= 16) e = run_router<T, 16, 1>(L, x, Wg, bias, R, blockhist, s);
   else if (L.N <= 32) e = run_router<T, 32, 1>(L, x, Wg, bias, R, blockhist, s);
   else e = run_router<T, 64, 1>(L, x, Wg, bias, R, blockhist, s);
   if (e != hipSuccess) return e;
