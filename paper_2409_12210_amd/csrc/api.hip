@@ -56,7 +56,6 @@ LayerDims make_dims(const modse_desc* desc, int64_t T) {
     L.order[e] = e;
   }
   std::stable_sort(L.order, L.order + L.N, [&](int a, int b) { return L.f[a] > L.f[b]; });
-  L.ldt = (int32_t)(align_up((size_t)T * L.k, MODSE_KPAD) + (size_t)MODSE_KPAD * L.N);
   return L;
 }
 
@@ -111,29 +110,20 @@ SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
 }
 
 struct BwdLayout {
-  size_t plan[6], W1T, W3T, W2T, Xp, XpT, dO, dOT, HT, dA, dB, dAT, dBT, dXp, dg, dWg_partial, total;
+  size_t plan[5], Xp, dO, dA, dB, dXp, dg, dWg_partial, total;
 };
 
 BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
   BwdLayout w;
   Carver c;
-  const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k, F = L.foff[L.N];
+  const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k;
   const size_t h = hidden_elems_max(L) * es;
-  const size_t hp = (hidden_elems_max(L) + (size_t)MODSE_KPAD * F) * es;  // token axis padded per expert
   const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
-  for (int i = 0; i < 6; ++i) w.plan[i] = c.take(sizeof(GemmPlan));
-  w.W1T = c.take(F * L.d * es);
-  w.W3T = c.take(F * L.d * es);
-  w.W2T = c.take(F * L.d * es);
+  for (int i = 0; i < 5; ++i) w.plan[i] = c.take(sizeof(GemmPlan));
   w.Xp = c.take(Tk * L.d * es);
-  w.XpT = c.take((size_t)L.d * L.ldt * es);
   w.dO = c.take(Tk * L.d * es);
-  w.dOT = c.take((size_t)L.d * L.ldt * es);
-  w.HT = c.take(hp);
   w.dA = c.take(h);
   w.dB = c.take(h);
-  w.dAT = c.take(hp);
-  w.dBT = c.take(hp);
   w.dXp = c.take(Tk * L.d * es);
   w.dg = c.take(Tk * 4);
   w.dWg_partial = c.take(nb * L.d * L.N * 4);
@@ -328,16 +318,10 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
   float* dg = reinterpret_cast<float*>(wsb + w.dg);
   HIP_TRY(launch_gather_rows(L, dt, x, R, Xp, s));
   HIP_TRY(launch_bwd_prep(L, dt, dY, sb + sl.O, R, dO, dg, s));
-  HIP_TRY(launch_transpose_weights(L, dt, W1, W3, W2, wsb + w.W1T, wsb + w.W3T, wsb + w.W2T, s));
-  HIP_TRY(launch_transpose_act(L, dt, 0, R.counts, R.offsets, Xp, wsb + w.XpT, s));
-  HIP_TRY(launch_transpose_act(L, dt, 0, R.counts, R.offsets, dO, wsb + w.dOT, s));
-  HIP_TRY(launch_transpose_act(L, dt, 1, R.counts, R.offsets, sb + sl.H, wsb + w.HT, s));
-
   BwdPlanArgs pa;
   std::memset(&pa, 0, sizeof(pa));
-  pa.dO = dO; pa.Apre = sb + sl.Apre; pa.Bpre = sb + sl.Bpre;
-  pa.W1T = wsb + w.W1T; pa.W3T = wsb + w.W3T; pa.W2T = wsb + w.W2T;
-  pa.XpT = wsb + w.XpT; pa.dOT = wsb + w.dOT; pa.HT = wsb + w.HT; pa.dAT = wsb + w.dAT; pa.dBT = wsb + w.dBT;
+  pa.Xp = Xp; pa.dO = dO; pa.H = sb + sl.H; pa.Apre = sb + sl.Apre; pa.Bpre = sb + sl.Bpre;
+  pa.W1 = W1; pa.W3 = W3; pa.W2 = W2;
   pa.dA = wsb + w.dA; pa.dB = wsb + w.dB; pa.dXp = wsb + w.dXp;
   pa.dW1 = dW1; pa.dW3 = dW3; pa.dW2 = dW2;
   pa.dh = reinterpret_cast<GemmPlan*>(wsb + w.plan[0]);
@@ -352,10 +336,6 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
   stamp.mark(MODSE_STAGE_BWD_PREP);
 
   HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU_BWD, pa.dh, 0, 0, tiles_bound(L, T, pa.dh_tile, true), s));
-  stamp.mark(MODSE_STAGE_BWD_DGRAD);
-  HIP_TRY(launch_transpose_act(L, dt, 1, R.counts, R.offsets, pa.dA, wsb + w.dAT, s));
-  HIP_TRY(launch_transpose_act(L, dt, 1, R.counts, R.offsets, pa.dB, wsb + w.dBT, s));
-  stamp.mark(MODSE_STAGE_BWD_PREP);
   HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_DUALK, pa.dx, 0, 0, tiles_bound(L, T, pa.dx_tile, false), s));
   stamp.mark(MODSE_STAGE_BWD_DGRAD);
 

@@ -7,7 +7,6 @@
 
 #define MODSE_MAX_EXPERTS 64
 #define MODSE_ROUTE_TOKENS_PER_BLOCK 32  // tokens handled by one block of the router / scatter kernels
-#define MODSE_KPAD 64                    // token-axis padding of transposed activations (backward)
 
 typedef __bf16 bf16_t;
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
@@ -18,17 +17,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---------------------------------------------------------------- element helpers
-template <typename T>
-struct Elem;
-template <>
-struct Elem<float> {
-  static constexpr modse_dtype dtype = MODSE_F32;
-};
-template <>
-struct Elem<bf16_t> {
-  static constexpr modse_dtype dtype = MODSE_BF16;
-};
-
 // 8 consecutive elements -> 8 floats
 __device__ inline void load8(const float* p, float v[8]) {
   const f32x4 a = *reinterpret_cast<const f32x4*>(p);
@@ -73,7 +61,8 @@ __device__ inline void store4(bf16_t* p, const float v[4]) {
 }
 
 // ---------------------------------------------------------------- grouped GEMM
-// One problem per expert:  C[M,N] (+)= A[M,K] B[N,K]^T (+ A2[M,K] B2[N,K]^T), operands with K contiguous.
+// One problem per expert:  C[M,N] (+)= A B^T (+ A2 B2^T).  How A and B lie in memory is a property of the
+// kernel instantiation (GemmLayout); lda / ldb are the row strides of the stored matrices.
 struct GemmProblem {
   const void* A;
   const void* B;
@@ -105,6 +94,12 @@ enum GemmEpilogue {
   EPI_STORE_DUALK = 4, // C = acc over two operand pairs (A,B) and (A2,B2)
 };
 
+enum GemmLayout {
+  LAYOUT_TN = 0,    // A [M,K], B [N,K]: both K-contiguous (forward GEMMs)
+  LAYOUT_B_KN = 2,  // A [M,K], B [K,N]                    (data gradients: weights as they lie)
+  LAYOUT_AB_K = 3,  // A [K,M], B [K,N]                    (weight gradients: contraction over tokens)
+};
+
 // Host-known description of the layer handed to kernels by value.
 struct LayerDims {
   int32_t d, N, k;
@@ -112,7 +107,6 @@ struct LayerDims {
   int32_t f[MODSE_MAX_EXPERTS];
   int32_t foff[MODSE_MAX_EXPERTS + 1];
   int32_t order[MODSE_MAX_EXPERTS];  // experts by descending width (ties: lower index)
-  int32_t ldt;                       // row stride of token-transposed activations (backward)
 };
 
 struct RoutingPtrs {
@@ -157,9 +151,8 @@ hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* co
                            const FwdPlanArgs& a, hipStream_t s);
 
 struct BwdPlanArgs {
-  const void *dO, *Apre, *Bpre;
-  const void *W1T, *W3T, *W2T;            // transposed weights
-  const void *XpT, *dOT, *HT, *dAT, *dBT;  // token-transposed activations, K padded to MODSE_KPAD per expert
+  const void *Xp, *dO, *H, *Apre, *Bpre;
+  const void *W1, *W3, *W2;
   void *dA, *dB, *dXp;
   float *dW1, *dW3, *dW2;
   GemmPlan *dh, *dx, *wg1, *wg3, *wg2;
@@ -167,11 +160,3 @@ struct BwdPlanArgs {
 };
 hipError_t launch_plan_bwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
                            const BwdPlanArgs& a, hipStream_t s);
-
-// Transposes.  Weights: per expert, host-known shapes.  Activations: rows per expert are counts[e] (device
-// side); destination columns are padded with zeros up to a multiple of MODSE_KPAD.
-hipError_t launch_transpose_weights(const LayerDims& L, modse_dtype dt, const void* W1, const void* W3,
-                                    const void* W2, void* W1T, void* W3T, void* W2T, hipStream_t s);
-// kind 0: dense [T*k, d] -> [d, ldt];  kind 1: ragged per expert [n_e, f_e] -> [f_e, npad_e]
-hipError_t launch_transpose_act(const LayerDims& L, modse_dtype dt, int kind, const int32_t* counts,
-                                const int32_t* offsets, const void* src, void* dst, hipStream_t s);

@@ -2,6 +2,10 @@
 // expert (known only on the device), N or K = the expert's own hidden width d_ff[e] (Sec. 3.1 of
 // arXiv 2409.12210).  A tiny plan kernel turns the device-side counts into a problem table and a tile
 // prefix; persistent GEMM workgroups walk the tile list without any host round trip.
+//
+// Operand layouts (GemmLayout): every tensor of the layer is used as it lies in memory.  The forward
+// GEMMs have both operands K-contiguous; the data-gradient GEMMs read the weights as [K, N]; the
+// weight-gradient GEMMs contract over tokens and read both activations as [K, M] and [K, N].
 #include "common.h"
 #include "gemm_bf16.h"
 #include "gemm_tiles.h"
@@ -12,15 +16,19 @@ using namespace modse_gemm;
 // ------------------------------------------------------------------------------------------------
 // float32 path: plain FMA tiles (parity configuration; no throughput claim)
 // ------------------------------------------------------------------------------------------------
-template <int EPI>
+template <int EPI, int LAYOUT>
 __global__ __launch_bounds__(256) void gg_f32_kernel(const GemmPlan* __restrict__ plan, int accumulate,
                                                      int save_pre) {
   constexpr int BM = 64, BN = 64, BK = 16;
   constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr bool A_T = (LAYOUT & 1) != 0, B_T = (LAYOUT & 2) != 0;
+  static_assert(!(B_T && NB == 2), "the two-matrix up-projection reads K-contiguous weights");
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[NB][BK][BN + 4];
   const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  // K-contiguous operand: thread loads 4 consecutive k of row tid/4; [K, X] operand: 4 consecutive x of K row tid/16
   const int lrow = tid / 4, lk = (tid % 4) * 4;
+  const int tk = tid / 16, tx4 = (tid % 16) * 4;
   const int total = plan->tile_start[plan->n_prob];
   for (int tile = first_tile_of_block(); tile < total; tile += gridDim.x) {
     TileCoord tc;
@@ -35,21 +43,27 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GemmPlan* __restrict_
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[q][i][j] = 0.f;
     const int arow = min(m0 + lrow, P.M - 1), brow = min(n0 + lrow, P.N - 1);
+    const int acol = min(m0 + tx4, P.M - 4), bcol = min(n0 + tx4, P.N - 4);  // M, N are multiples of 4
     const int npass = (EPI == EPI_STORE_DUALK) ? 2 : 1;
     for (int pass = 0; pass < npass; ++pass) {
-      const float* A = static_cast<const float*>(pass ? P.A2 : P.A) + (size_t)arow * P.lda + lk;
-      const float* B = static_cast<const float*>(pass ? P.B2 : P.B) + (size_t)brow * P.ldb + lk;
-      const float* B2 = NB == 2 ? static_cast<const float*>(P.B2) + (size_t)brow * P.ldb + lk : nullptr;
+      const float* A = static_cast<const float*>(pass ? P.A2 : P.A);
+      const float* B = static_cast<const float*>(pass ? P.B2 : P.B);
+      const float* B2 = static_cast<const float*>(P.B2);
       for (int k0 = 0; k0 < P.K; k0 += BK) {
-        const f32x4 av = *reinterpret_cast<const f32x4*>(A + k0);
-        const f32x4 bv = *reinterpret_cast<const f32x4*>(B + k0);
-        f32x4 b2v = {0.f, 0.f, 0.f, 0.f};
-        if (NB == 2) b2v = *reinterpret_cast<const f32x4*>(B2 + k0);
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        f32x4 av, bv, b2v = zero;
+        if (A_T) av = k0 + tk < P.K ? *reinterpret_cast<const f32x4*>(A + (size_t)(k0 + tk) * P.lda + acol) : zero;
+        else av = *reinterpret_cast<const f32x4*>(A + (size_t)arow * P.lda + k0 + lk);  // K % 16 == 0 here
+        if (B_T) bv = k0 + tk < P.K ? *reinterpret_cast<const f32x4*>(B + (size_t)(k0 + tk) * P.ldb + bcol) : zero;
+        else bv = *reinterpret_cast<const f32x4*>(B + (size_t)brow * P.ldb + k0 + lk);
+        if (NB == 2) b2v = *reinterpret_cast<const f32x4*>(B2 + (size_t)brow * P.ldb + k0 + lk);
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          As[lk + i][lrow] = av[i];
-          Bs[0][lk + i][lrow] = bv[i];
+          if (A_T) As[tk][tx4 + i] = av[i];
+          else As[lk + i][lrow] = av[i];
+          if (B_T) Bs[0][tk][tx4 + i] = bv[i];
+          else Bs[0][lk + i][lrow] = bv[i];
           if (NB == 2) Bs[NB - 1][lk + i][lrow] = b2v[i];
         }
         __syncthreads();
@@ -139,127 +153,65 @@ __global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, co
   finish_plan(a.down, i, on, L.N, a.down_tile.bm, a.down_tile.bn, s_tiles);
 }
 
-__device__ inline int pad_tokens(int n) { return (n + MODSE_KPAD - 1) / MODSE_KPAD * MODSE_KPAD; }
-
 __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
                                                       const int32_t* __restrict__ offsets, BwdPlanArgs a) {
   __shared__ int s_tiles[MODSE_MAX_EXPERTS];
   const int i = threadIdx.x;
   const bool on = i < L.N;
   const int e = on ? L.order[i] : 0;
-  size_t hoff = 0, hpoff = 0, poff = 0;
-  for (int q = 0; q < e; ++q) {
-    hoff += (size_t)counts[q] * L.f[q];
-    hpoff += (size_t)pad_tokens(counts[q]) * L.f[q];
-    poff += pad_tokens(counts[q]);
-  }
-  const int n_e = counts[e], npad = pad_tokens(n_e), f = L.f[e], d = L.d;
+  size_t hoff = 0;
+  for (int q = 0; q < e; ++q) hoff += (size_t)counts[q] * L.f[q];
+  const int n_e = counts[e], f = L.f[e], d = L.d;
   const size_t es = esize;
-  const size_t woff = (size_t)L.foff[e] * d;  // element offset of expert e in W1/W3/W2 and their transposes
-  if (on) {  // dh = dO W2, fused SwiGLU backward -> dA, dB
+  const size_t woff = (size_t)L.foff[e] * d;   // element offset of expert e in W1/W3/W2 and their gradients
+  const size_t roff = (size_t)offsets[e] * d;  // element offset of expert e's rows in [T*k, d] tensors
+  if (on) {  // dh = dO W2 (W2_e is [d, f]: a [K, N] operand), fused SwiGLU backward -> dA, dB
     GemmProblem P = {};
-    P.A = cadd(a.dO, (size_t)offsets[e] * d * es);
-    P.B = cadd(a.W2T, woff * es);  // [f, d]
+    P.A = cadd(a.dO, roff * es);
+    P.B = cadd(a.W2, woff * es);
     P.C = vadd(a.dA, hoff * es);
     P.C2 = vadd(a.dB, hoff * es);
     P.E1 = cadd(a.Apre, hoff * es);
     P.E2 = cadd(a.Bpre, hoff * es);
     P.M = n_e; P.N = f; P.K = d;
-    P.lda = d; P.ldb = d; P.ldc = f;
+    P.lda = d; P.ldb = f; P.ldc = f;
     a.dh->prob[i] = P;
   }
   finish_plan(a.dh, i, on, L.N, a.dh_tile.bm, a.dh_tile.bn, s_tiles);
-  if (on) {  // dXp = dA W1 + dB W3
+  if (on) {  // dXp = dA W1 + dB W3 (W1_e, W3_e are [f, d]: [K, N] operands)
     GemmProblem P = {};
     P.A = cadd(a.dA, hoff * es);
-    P.B = cadd(a.W1T, woff * es);  // [d, f]
+    P.B = cadd(a.W1, woff * es);
     P.A2 = cadd(a.dB, hoff * es);
-    P.B2 = cadd(a.W3T, woff * es);
-    P.C = vadd(a.dXp, (size_t)offsets[e] * d * es);
+    P.B2 = cadd(a.W3, woff * es);
+    P.C = vadd(a.dXp, roff * es);
     P.M = n_e; P.N = d; P.K = f;
-    P.lda = f; P.ldb = f; P.ldc = d;
+    P.lda = f; P.ldb = d; P.ldc = d;
     a.dx->prob[i] = P;
   }
   finish_plan(a.dx, i, on, L.N, a.dx_tile.bm, a.dx_tile.bn, s_tiles);
-  for (int which = 0; which < 2; ++which) {  // dW1 = dA^T Xp, dW3 = dB^T Xp
+  for (int which = 0; which < 2; ++which) {  // dW1 = dA^T Xp, dW3 = dB^T Xp: contraction over the expert's tokens
     if (on) {
       GemmProblem P = {};
-      P.A = cadd(which ? a.dBT : a.dAT, hpoff * es);  // [f, npad]
-      P.B = cadd(a.XpT, poff * es);                   // [d, ldt]
+      P.A = cadd(which ? a.dB : a.dA, hoff * es);  // [K = n_e, M = f]
+      P.B = cadd(a.Xp, roff * es);                  // [K = n_e, N = d]
       P.C = (which ? a.dW3 : a.dW1) + woff;
-      P.M = f; P.N = d; P.K = npad;
-      P.lda = npad; P.ldb = L.ldt; P.ldc = d;
+      P.M = f; P.N = d; P.K = n_e;
+      P.lda = f; P.ldb = d; P.ldc = d;
       (which ? a.wg3 : a.wg1)->prob[i] = P;
     }
     finish_plan(which ? a.wg3 : a.wg1, i, on, L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
   }
   if (on) {  // dW2 = dO^T H
     GemmProblem P = {};
-    P.A = cadd(a.dOT, poff * es);   // [d, ldt]
-    P.B = cadd(a.HT, hpoff * es);   // [f, npad]
+    P.A = cadd(a.dO, roff * es);  // [K = n_e, M = d]
+    P.B = cadd(a.H, hoff * es);   // [K = n_e, N = f]
     P.C = a.dW2 + woff;
-    P.M = d; P.N = f; P.K = npad;
-    P.lda = L.ldt; P.ldb = npad; P.ldc = f;
+    P.M = d; P.N = f; P.K = n_e;
+    P.lda = d; P.ldb = f; P.ldc = f;
     a.wg2->prob[i] = P;
   }
   finish_plan(a.wg2, i, on, L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
-}
-
-// ------------------------------------------------------------------------------------------------
-// transposes (backward): 64x64 tiles through LDS
-// ------------------------------------------------------------------------------------------------
-// dst[c][r] = src[r][c] for r < rows, c < cols; dst columns rows..rows_pad-1 are zero-filled.
-template <typename T>
-__device__ inline void transpose_tile(const T* __restrict__ src, int lds, int rows, int cols, T* __restrict__ dst,
-                                      int ldd, int rows_pad, int r0, int c0) {
-  __shared__ T tile[64][65];
-  const int tx = threadIdx.x % 64, ty = threadIdx.x / 64;  // 256 threads
-  for (int i = ty; i < 64; i += 4) {
-    const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < rows && c < cols) ? src[(size_t)r * lds + c] : (T)0.f;
-  }
-  __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int c = c0 + i, r = r0 + tx;
-    if (c < cols && r < rows_pad) dst[(size_t)c * ldd + r] = tile[tx][i];
-  }
-}
-
-// weights: mode 0: W [F,d] row blocks [f_e, d] -> [d, f_e] at d*foff[e];  mode 1: the reverse
-template <typename T>
-__global__ __launch_bounds__(256) void transpose_weights_kernel(LayerDims L, int mode, const T* __restrict__ src,
-                                                                T* __restrict__ dst) {
-  const int e = blockIdx.y;
-  const int rows = mode == 0 ? L.f[e] : L.d, cols = mode == 0 ? L.d : L.f[e];
-  const int ct = (cols + 63) / 64;
-  const int rt = blockIdx.x / ct, cti = blockIdx.x % ct;
-  if (rt * 64 >= rows) return;
-  const size_t off = (size_t)L.foff[e] * L.d;
-  transpose_tile<T>(src + off, cols, rows, cols, dst + off, rows, rows, rt * 64, cti * 64);
-}
-
-// activations, kind 0: src [T*k, d] (expert e = rows offsets[e]..) -> dst [d, ldt], expert e at column poff[e]
-//              kind 1: src ragged [n_e, f_e] at hoff[e] -> dst [f_e, npad_e] at hpoff[e]
-template <typename T>
-__global__ __launch_bounds__(256) void transpose_act_kernel(LayerDims L, int kind, const int32_t* __restrict__ counts,
-                                                            const int32_t* __restrict__ offsets,
-                                                            const T* __restrict__ src, T* __restrict__ dst) {
-  const int e = blockIdx.y;
-  const int n_e = counts[e], npad = pad_tokens(n_e);
-  const int cols = kind == 0 ? L.d : L.f[e];
-  const int ct = (cols + 63) / 64;
-  const int rt = blockIdx.x / ct, cti = blockIdx.x % ct;
-  if (rt * 64 >= npad) return;
-  size_t hoff = 0, hpoff = 0, poff = 0;
-  for (int q = 0; q < e; ++q) {
-    hoff += (size_t)counts[q] * L.f[q];
-    hpoff += (size_t)pad_tokens(counts[q]) * L.f[q];
-    poff += pad_tokens(counts[q]);
-  }
-  if (kind == 0)
-    transpose_tile<T>(src + (size_t)offsets[e] * L.d, L.d, n_e, cols, dst + poff, L.ldt, npad, rt * 64, cti * 64);
-  else
-    transpose_tile<T>(src + hoff, cols, n_e, cols, dst + hpoff, npad, npad, rt * 64, cti * 64);
 }
 
 int num_cus() {
@@ -274,23 +226,23 @@ int num_cus() {
   return n;
 }
 
-template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI>
+template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI, int LAYOUT>
 hipError_t run_bf16(const GemmPlan* plan, int accumulate, int save_pre, int64_t max_tiles, hipStream_t s) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   int64_t grid = num_cus();  // the two LDS stages fill a CU: one persistent workgroup per CU
   if (max_tiles < grid) grid = max_tiles;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL((gg_bf16_kernel<BM, BN, NB, WAVES_M, WAVES_N, EPI>), dim3((unsigned)grid), dim3(NT), 0, s, plan,
-                     accumulate, save_pre);
+  hipLaunchKernelGGL((gg_bf16_kernel<BM, BN, NB, WAVES_M, WAVES_N, EPI, LAYOUT>), dim3((unsigned)grid), dim3(NT), 0, s,
+                     plan, accumulate, save_pre);
   return hipGetLastError();
 }
 
-template <int EPI>
+template <int EPI, int LAYOUT>
 hipError_t run_f32(const GemmPlan* plan, int accumulate, int save_pre, int64_t max_tiles, hipStream_t s) {
   int64_t grid = (int64_t)num_cus() * 8;
   if (max_tiles < grid) grid = max_tiles;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL((gg_f32_kernel<EPI>), dim3((unsigned)grid), dim3(256), 0, s, plan, accumulate, save_pre);
+  hipLaunchKernelGGL((gg_f32_kernel<EPI, LAYOUT>), dim3((unsigned)grid), dim3(256), 0, s, plan, accumulate, save_pre);
   return hipGetLastError();
 }
 
@@ -303,27 +255,31 @@ TileShape gemm_tile_shape(modse_dtype dt, int epilogue, int64_t T) {
   return {256, 256};
 }
 
+// The epilogue fixes the operand layout: forward GEMMs are K-contiguous on both sides, data gradients read
+// the weights as [K, N], weight gradients read both activations token-major.
 hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* plan, int accumulate, int save_pre,
                                int64_t max_tiles, hipStream_t s) {
   if (dt == MODSE_F32) {
     switch (epilogue) {
-      case EPI_STORE: return run_f32<EPI_STORE>(plan, accumulate, save_pre, max_tiles, s);
-      case EPI_STORE_F32: return run_f32<EPI_STORE_F32>(plan, accumulate, save_pre, max_tiles, s);
-      case EPI_SWIGLU: return run_f32<EPI_SWIGLU>(plan, accumulate, save_pre, max_tiles, s);
-      case EPI_SWIGLU_BWD: return run_f32<EPI_SWIGLU_BWD>(plan, accumulate, save_pre, max_tiles, s);
-      case EPI_STORE_DUALK: return run_f32<EPI_STORE_DUALK>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_STORE: return run_f32<EPI_STORE, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_SWIGLU: return run_f32<EPI_SWIGLU, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_SWIGLU_BWD: return run_f32<EPI_SWIGLU_BWD, LAYOUT_B_KN>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_STORE_DUALK: return run_f32<EPI_STORE_DUALK, LAYOUT_B_KN>(plan, accumulate, save_pre, max_tiles, s);
+      case EPI_STORE_F32: return run_f32<EPI_STORE_F32, LAYOUT_AB_K>(plan, accumulate, save_pre, max_tiles, s);
     }
     return hipErrorInvalidValue;
   }
   switch (epilogue) {
-    case EPI_STORE: return run_bf16<256, 256, 1, 4, 2, EPI_STORE>(plan, accumulate, save_pre, max_tiles, s);
-    case EPI_STORE_F32:
-      return run_bf16<256, 256, 1, 4, 2, EPI_STORE_F32>(plan, accumulate, save_pre, max_tiles, s);
-    case EPI_SWIGLU: return run_bf16<256, 128, 2, 4, 2, EPI_SWIGLU>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_STORE:
+      return run_bf16<256, 256, 1, 4, 2, EPI_STORE, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_SWIGLU:
+      return run_bf16<256, 128, 2, 4, 2, EPI_SWIGLU, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);
     case EPI_SWIGLU_BWD:
-      return run_bf16<256, 256, 1, 4, 2, EPI_SWIGLU_BWD>(plan, accumulate, save_pre, max_tiles, s);
+      return run_bf16<256, 256, 1, 4, 2, EPI_SWIGLU_BWD, LAYOUT_B_KN>(plan, accumulate, save_pre, max_tiles, s);
     case EPI_STORE_DUALK:
-      return run_bf16<256, 256, 1, 4, 2, EPI_STORE_DUALK>(plan, accumulate, save_pre, max_tiles, s);
+      return run_bf16<256, 256, 1, 4, 2, EPI_STORE_DUALK, LAYOUT_B_KN>(plan, accumulate, save_pre, max_tiles, s);
+    case EPI_STORE_F32:
+      return run_bf16<256, 256, 1, 4, 2, EPI_STORE_F32, LAYOUT_AB_K>(plan, accumulate, save_pre, max_tiles, s);
   }
   return hipErrorInvalidValue;
 }
@@ -337,41 +293,5 @@ hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* co
 hipError_t launch_plan_bwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
                            const BwdPlanArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(plan_bwd_kernel, dim3(1), dim3(64), 0, s, L, dt == MODSE_F32 ? 4 : 2, counts, offsets, a);
-  return hipGetLastError();
-}
-
-template <typename T>
-static hipError_t transpose_weights_typed(const LayerDims& L, const T* W1, const T* W3, const T* W2, T* W1T, T* W3T,
-                                          T* W2T, hipStream_t s) {
-  int fmax = 0;
-  for (int e = 0; e < L.N; ++e) fmax = L.f[e] > fmax ? L.f[e] : fmax;
-  const unsigned gx = ((fmax + 63) / 64) * ((L.d + 63) / 64);
-  hipLaunchKernelGGL((transpose_weights_kernel<T>), dim3(gx, L.N), dim3(256), 0, s, L, 0, W1, W1T);
-  hipLaunchKernelGGL((transpose_weights_kernel<T>), dim3(gx, L.N), dim3(256), 0, s, L, 0, W3, W3T);
-  hipLaunchKernelGGL((transpose_weights_kernel<T>), dim3(gx, L.N), dim3(256), 0, s, L, 1, W2, W2T);
-  return hipGetLastError();
-}
-
-hipError_t launch_transpose_weights(const LayerDims& L, modse_dtype dt, const void* W1, const void* W3,
-                                    const void* W2, void* W1T, void* W3T, void* W2T, hipStream_t s) {
-  if (dt == MODSE_F32)
-    return transpose_weights_typed<float>(L, (const float*)W1, (const float*)W3, (const float*)W2, (float*)W1T,
-                                          (float*)W3T, (float*)W2T, s);
-  return transpose_weights_typed<bf16_t>(L, (const bf16_t*)W1, (const bf16_t*)W3, (const bf16_t*)W2, (bf16_t*)W1T,
-                                         (bf16_t*)W3T, (bf16_t*)W2T, s);
-}
-
-hipError_t launch_transpose_act(const LayerDims& L, modse_dtype dt, int kind, const int32_t* counts,
-                                const int32_t* offsets, const void* src, void* dst, hipStream_t s) {
-  int fmax = 0;
-  for (int e = 0; e < L.N; ++e) fmax = L.f[e] > fmax ? L.f[e] : fmax;
-  const int cols = kind == 0 ? L.d : fmax;
-  const unsigned gx = ((L.T + 63) / 64 + 1) * ((cols + 63) / 64);
-  if (dt == MODSE_F32)
-    hipLaunchKernelGGL((transpose_act_kernel<float>), dim3(gx, L.N), dim3(256), 0, s, L, kind, counts, offsets,
-                       (const float*)src, (float*)dst);
-  else
-    hipLaunchKernelGGL((transpose_act_kernel<bf16_t>), dim3(gx, L.N), dim3(256), 0, s, L, kind, counts, offsets,
-                       (const bf16_t*)src, (bf16_t*)dst);
   return hipGetLastError();
 }

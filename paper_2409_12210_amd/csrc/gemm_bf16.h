@@ -80,13 +80,19 @@ struct StepCursor {
   bool valid;
 };
 
-template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI>
+// LAYOUT bit 0: A is stored [K, M] (M contiguous) instead of [M, K]; bit 1: B is stored [K, N].  Such an
+// operand keeps its memory order in LDS (64 rows of K, 512 bytes each, 32-byte chunk index XOR-ed with
+// 2 * (k & 3)) and its MFMA fragments are read with ds_read_b64_tr_b16, which hands lane i of a 16-lane
+// group the i-th column of a 4 x 16 block of 16-bit elements: 4 consecutive K for one M (or N).
+template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI, int LAYOUT = 0>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const GemmPlan* __restrict__ plan,
                                                                         int accumulate, int save_pre) {
   using Cfg = Bf16Tile<BM, BN, NB, WAVES_M, WAVES_N>;
   constexpr int BK = Cfg::BK, MI = Cfg::MI, NI = Cfg::NI, UA = Cfg::UA, UPW = Cfg::UPW, STAGE = Cfg::STAGE;
   constexpr int WM = Cfg::WM, WN = Cfg::WN;
   constexpr int SLICE = UPW / MODSE_DMA_SPREAD;
+  constexpr bool A_T = (LAYOUT & 1) != 0, B_T = (LAYOUT & 2) != 0;
+  static_assert(!(A_T && BM != 256) && !(B_T && (BN != 256 || NB != 1)), "transposed operands use 256-wide tiles");
   static_assert(UA % UPW == 0 && (BN / 8) % UPW == 0, "all load units of a wave must belong to one operand");
   __shared__ __attribute__((aligned(1024))) char stages[2 * STAGE];
 
@@ -105,6 +111,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   const int a_frag = (wm * WM + (lane & 31)) * 128;
   const int b_frag = BM * 128 + (wn * WN + (lane & 31)) * 128;
   const int khalf = lane >> 5, lsw = (lane >> 1) & 7;
+  // transposed operands: this lane's row inside a load unit (2 rows of 32 chunks) and its chunk
+  const int t_row = lane >> 5, t_chunk = lane & 31;
+  const bool loads_a = wave * UPW < UA;                       // wave-uniform: which operand this wave loads
+  const bool loads_t = loads_a ? A_T : B_T;                   // ... and whether it is a transposed one
 
   auto open_tile = [&](StepCursor& c, GemmProblem& Q) {
     TileCoord tc;
@@ -130,6 +140,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     }
   };
   auto issue_offsets = [&]() {
+    if (loads_t) {  // unit = K rows 2u, 2u+1; LDS position (k, p) holds 16-byte chunk p ^ (4 * (k & 3))
+#pragma unroll
+      for (int i = 0; i < UPW; ++i) {
+        const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
+        const int k = 2 * ul + t_row;
+        const int c16 = t_chunk ^ (4 * (k & 3));
+        const int x0 = loads_a ? ic.m0 : ic.n0, X = loads_a ? IP.M : IP.N, ld = loads_a ? IP.lda : IP.ldb;
+        ioff[i] = (uint32_t)(k * ld + min(x0 + c16 * 8, X - 8)) * 2u;  // columns past the end repeat the last chunk
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < UPW; ++i) {
       const int u = wave * UPW + i;
@@ -155,10 +176,19 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     const int pass = (EPI == EPI_STORE_DUALK && ic.step >= ic.nk) ? 1 : 0;
     const int k0 = (ic.step - pass * ic.nk) * BK;
     const uint32_t dst = lds_mine + buf * STAGE;
-    const char* base = my_operand(pass) + (size_t)k0 * 2;
+    const int kstride = loads_t ? (loads_a ? IP.lda : IP.ldb) : 1;  // elements between consecutive K
+    const char* base = my_operand(pass) + (size_t)k0 * kstride * 2;
     if (k0 + BK <= IP.K) {
 #pragma unroll
       for (int i = first; i < first + count; ++i) dma_b128_s(base, ioff[i], dst + i * 1024);
+    } else if (loads_t) {  // partial last step: K rows beyond K read zeros
+#pragma unroll
+      for (int i = first; i < first + count; ++i) {
+        const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
+        const char* src = base + ioff[i];
+        if (k0 + 2 * ul + t_row >= IP.K) src = reinterpret_cast<const char*>(g_zero_chunk);
+        dma_b128(src, dst + i * 1024);
+      }
     } else {  // last step of a pass when K % 64 != 0: chunks beyond K read zeros
 #pragma unroll
       for (int i = first; i < first + count; ++i) {
@@ -195,15 +225,47 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   // Fragments are double-buffered in registers: set (kk & 1) feeds the MFMAs of K slice kk while the
   // other set is being read from LDS.
   bf16x8 af[2][MI], bfr[2][NB][NI];
+  // Transposed operands.  Lane l = 16 * blk + s reads, for K slice kk and half h, the 8 bytes at
+  // K row kk*16 + (blk >> 1)*8 + h*4 + (s >> 2), column x = tile_x + 32*i + (blk & 1)*16 + 4*(s & 3); the
+  // instruction returns K rows +0..+3 of column tile_x + 32*i + (blk & 1)*16 + s.
+  int tr_a[MI], tr_b[NI];
+  {
+    const int blk = lane >> 4, sl = lane & 15, kq = sl >> 2;
+    const int rowbyte = ((blk >> 1) * 8 + kq) * 512 + (sl & 1) * 8;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int c16 = (wm * WM + i * 32 + (blk & 1) * 16) / 8 + ((sl & 3) >> 1);
+      tr_a[i] = rowbyte + ((c16 ^ (4 * kq)) << 4);
+    }
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int c16 = (wn * WN + j * 32 + (blk & 1) * 16) / 8 + ((sl & 3) >> 1);
+      tr_b[j] = BM * 128 + rowbyte + ((c16 ^ (4 * kq)) << 4);
+    }
+  }
+  auto read_tr = [&](const char* p) -> bf16x8 {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * 512));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  };
   auto load_frags = [&](const char* buf, int kk, int set) {
     const int sw = ((kk * 2 + khalf) ^ lsw) << 4;
 #pragma unroll
-    for (int i = 0; i < MI; ++i) af[set][i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + i * 32 * 128 + sw);
+    for (int i = 0; i < MI; ++i) {
+      if (A_T) af[set][i] = read_tr(buf + tr_a[i] + kk * 16 * 512);
+      else af[set][i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + i * 32 * 128 + sw);
+    }
 #pragma unroll
     for (int q = 0; q < NB; ++q)
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-        bfr[set][q][j] = *reinterpret_cast<const bf16x8*>(buf + b_frag + (q * BN + j * 32) * 128 + sw);
+      for (int j = 0; j < NI; ++j) {
+        if (B_T) bfr[set][q][j] = read_tr(buf + tr_b[j] + kk * 16 * 512);
+        else bfr[set][q][j] = *reinterpret_cast<const bf16x8*>(buf + b_frag + (q * BN + j * 32) * 128 + sw);
+      }
   };
   f32x16 acc[NB][MI][NI];
   auto mfma_block = [&](int set) {
