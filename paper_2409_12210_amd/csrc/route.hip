@@ -57,6 +57,20 @@ __device__ inline int bitrev(int v) {
   return r;
 }
 
+// NE consecutive elements -> floats, with the widest aligned vector loads
+template <int NE, typename T>
+__device__ inline void load_row(const T* p, float* out) {
+  if constexpr (NE % 8 == 0) {
+#pragma unroll
+    for (int e = 0; e < NE; e += 8) load8(p + e, out + e);
+  } else if constexpr (NE == 4) {
+    load4(p, out);
+  } else {
+#pragma unroll
+    for (int e = 0; e < NE; ++e) out[e] = (float)p[e];
+  }
+}
+
 // One block routes TPB consecutive tokens.  blockhist[b][0..N-1] = this block's per-expert assignment
 // counts, blockhist[b][N] = its near-tie token count.
 template <typename T, int NE, int TOK>
@@ -89,9 +103,15 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
       for (int i = 0; i < 8; ++i) {  // one W_gate row at a time keeps the register footprint small
         double w[NE];
         const T* wrow = Wg + (size_t)(c + i) * N;
-        // columns e >= N repeat the last expert; their sums are never looked at
+        float wf[NE];
+        if (N == NE) {
+          load_row<NE>(wrow, wf);  // one vector load per W_gate row
+        } else {  // columns e >= N repeat the last expert; their sums are never looked at
 #pragma unroll
-        for (int e = 0; e < NE; ++e) w[e] = (double)(float)wrow[min(e, N - 1)];
+          for (int e = 0; e < NE; ++e) wf[e] = (float)wrow[min(e, N - 1)];
+        }
+#pragma unroll
+        for (int e = 0; e < NE; ++e) w[e] = (double)wf[e];
 #pragma unroll
         for (int tt = 0; tt < TOK; ++tt) {
           const double xd = (double)xv[tt][i];
@@ -405,14 +425,100 @@ __global__ __launch_bounds__(ROUTE_THREADS) void bwd_router_kernel(
   }
 }
 
-// dW_gate[i] (+)= sum_b partial[b][i], fixed summation order (deterministic)
+// Same as bwd_router_kernel for N <= 8, one pass over the data: a thread owns 8 columns of d for all
+// BR_TOK tokens of the block, keeps the 8 x 8 slice of W_gate and of the dW_gate partial in registers, and
+// per token reads x and the two dXp rows once (16-byte loads, a full row per block instruction).
+constexpr int BR_TOK = 64;
+template <typename T>
+__global__ __launch_bounds__(ROUTE_THREADS) void bwd_router8_kernel(
+    const T* __restrict__ x, const T* __restrict__ Wg, const T* __restrict__ dXp, const float* __restrict__ dg,
+    int ntok, int d, int N, int top_k, const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+    const int32_t* __restrict__ row_of, T* __restrict__ dX, float* __restrict__ partial) {
+  __shared__ __attribute__((aligned(16))) float s_dl[BR_TOK][8];
+  __shared__ int s_row[BR_TOK][2];
+  const int tid = threadIdx.x;
+  const int t0 = blockIdx.x * BR_TOK;
+  for (int i = tid; i < BR_TOK * 8; i += ROUTE_THREADS) (&s_dl[0][0])[i] = 0.f;
+  __syncthreads();
+  if (tid < BR_TOK && t0 + tid < ntok) {
+    const int t = t0 + tid;
+    float g[2] = {0.f, 0.f}, dgv[2] = {0.f, 0.f};
+    int idx[2] = {0, 0};
+    float mean = 0.f;
+    for (int j = 0; j < top_k; ++j) {
+      const int r = row_of[(size_t)t * top_k + j];
+      s_row[tid][j] = r;
+      idx[j] = topk_idx[(size_t)t * top_k + j];
+      g[j] = topk_w[(size_t)t * top_k + j];
+      dgv[j] = dg[r];
+      mean += g[j] * dgv[j];
+    }
+    for (int j = 0; j < top_k; ++j) s_dl[tid][idx[j]] = g[j] * (dgv[j] - mean);
+  }
+  __syncthreads();
+  const int nt = min(BR_TOK, ntok - t0);
+  for (int c = tid * 8; c < d; c += ROUTE_THREADS * 8) {
+    float wg[8][8], acc[8][8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      if (N == 8) {
+        load8(Wg + (size_t)(c + q) * 8, wg[q]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wg[q][e] = e < N ? (float)Wg[(size_t)(c + q) * N + e] : 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
+    }
+    for (int tl = 0; tl < nt; ++tl) {
+      const int t = t0 + tl;
+      float dlv[8], xv[8], a[8], o[8];
+      load8(&s_dl[tl][0], dlv);
+      load8(x + (size_t)t * d + c, xv);
+      load8(dXp + (size_t)s_row[tl][0] * d + c, a);
+      if (top_k == 2) {
+        float b[8];
+        load8(dXp + (size_t)s_row[tl][1] * d + c, b);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) a[q] += b[q];
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        float go = a[q];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          go = fmaf(wg[q][e], dlv[e], go);
+          acc[q][e] = fmaf(xv[q], dlv[e], acc[q][e]);
+        }
+        o[q] = go;
+      }
+      store8(dX + (size_t)t * d + c, o);
+    }
+    float* out = partial + ((size_t)blockIdx.x * d + c) * N;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < N) out[q * N + e] = acc[q][e];
+  }
+}
+
+// dW_gate[i] (+)= sum_b partial[b][i] in a fixed order (deterministic): 64 outputs per block, the blocks'
+// partials are split over the 4 waves and combined through LDS.
 __global__ __launch_bounds__(256) void dwg_reduce_kernel(const float* __restrict__ partial, int nb, int n,
                                                          int accumulate, float* __restrict__ dWg) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
+  __shared__ float s_part[4][64];
+  const int li = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + li;
   float acc = 0.f;
-  for (int b = 0; b < nb; ++b) acc += partial[(size_t)b * n + i];
-  dWg[i] = accumulate ? dWg[i] + acc : acc;
+  if (i < n)
+    for (int b = part; b < nb; b += 4) acc += partial[(size_t)b * n + i];
+  s_part[part][li] = acc;
+  __syncthreads();
+  if (part == 0 && i < n) {
+    const float v = (s_part[0][li] + s_part[1][li]) + (s_part[2][li] + s_part[3][li]);
+    dWg[i] = accumulate ? dWg[i] + v : v;
+  }
 }
 
 template <typename T, int NE, int TOK>
@@ -496,20 +602,22 @@ hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x,
 hipError_t launch_bwd_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const void* dXp,
                              const float* dg, const RoutingPtrs& R, void* dX, float* dWg_partial, float* dW_gate,
                              int accumulate, hipStream_t s) {
-  const int nb = (L.T + TPB - 1) / TPB;
-  if (dt == MODSE_F32)
-    hipLaunchKernelGGL((bwd_router_kernel<float>), dim3(nb), dim3(ROUTE_THREADS), 0, s, static_cast<const float*>(x),
+  const bool small_n = L.N <= 8;
+  const int nb = small_n ? (L.T + BR_TOK - 1) / BR_TOK : (L.T + TPB - 1) / TPB;
+  if (dt == MODSE_F32) {
+    auto kern = small_n ? bwd_router8_kernel<float> : bwd_router_kernel<float>;
+    hipLaunchKernelGGL(kern, dim3(nb), dim3(ROUTE_THREADS), 0, s, static_cast<const float*>(x),
                        static_cast<const float*>(W_gate), static_cast<const float*>(dXp), dg, L.T, L.d, L.N, L.k,
                        R.topk_idx, R.topk_w, R.row_of, static_cast<float*>(dX), dWg_partial);
-  else
-    hipLaunchKernelGGL((bwd_router_kernel<bf16_t>), dim3(nb), dim3(ROUTE_THREADS), 0, s,
-                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(W_gate),
-                       static_cast<const bf16_t*>(dXp), dg, L.T, L.d, L.N, L.k, R.topk_idx, R.topk_w, R.row_of,
-                       static_cast<bf16_t*>(dX), dWg_partial);
+  } else {
+    auto kern = small_n ? bwd_router8_kernel<bf16_t> : bwd_router_kernel<bf16_t>;
+    hipLaunchKernelGGL(kern, dim3(nb), dim3(ROUTE_THREADS), 0, s, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(W_gate), static_cast<const bf16_t*>(dXp), dg, L.T, L.d, L.N, L.k,
+                       R.topk_idx, R.topk_w, R.row_of, static_cast<bf16_t*>(dX), dWg_partial);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int n = L.d * L.N;
-  hipLaunchKernelGGL(dwg_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, s, dWg_partial, nb, n, accumulate,
-                     dW_gate);
+  hipLaunchKernelGGL(dwg_reduce_kernel, dim3((n + 63) / 64), dim3(256), 0, s, dWg_partial, nb, n, accumulate, dW_gate);
   return hipGetLastError();
 }
