@@ -48,6 +48,10 @@ __device__ __forceinline__ void dma_b128_s(const void* base, uint32_t voff, uint
                "v"(voff), "s"(uniform_ptr(base))
                : "memory");
 }
+// 16-byte accesses through the global address space (a generic pointer would make them flat accesses)
+typedef __attribute__((address_space(1))) bf16x8 global_bf16x8;
+__device__ __forceinline__ void global_store16(bf16_t* p, bf16x8 v) { *(global_bf16x8*)(uintptr_t)p = v; }
+__device__ __forceinline__ bf16x8 global_load16(const bf16_t* p) { return *(const global_bf16x8*)(uintptr_t)p; }
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
@@ -321,31 +325,154 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       }
       __builtin_amdgcn_sched_barrier(0);
       advance_issue();
-      if (next_stage) {
-        stage_barrier();
-        load_frags(stages + nbuf * STAGE, 0, 0);
-      }
+      // (after the very last step the barrier only retires the buffer: the epilogue stages through it)
+      stage_barrier();
+      if (next_stage) load_frags(stages + nbuf * STAGE, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       mfma_block(1);
     }
 
-    // epilogue: for register group r the lane holds columns n .. n+3 of row m
-    const int mrow = cc.m0 + wm * WM + (lane & 31);
-    const int ncol = cc.n0 + wn * WN + 4 * khalf;
+    // ---- epilogue.  For register group r of block (i, j) the lane holds columns n .. n+3 of row m.
+    if constexpr (EPI == EPI_STORE_F32) {
+      const int mrow = cc.m0 + wm * WM + (lane & 31);
+      const int ncol = cc.n0 + wn * WN + 4 * khalf;
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float a[4], b[4];
+          for (int r = 0; r < 4; ++r) {
+            float a[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            a[q] = acc[0][i][j][r * 4 + q];
-            b[q] = acc[NB - 1][i][j][r * 4 + q];
+            for (int q = 0; q < 4; ++q) a[q] = acc[0][i][j][r * 4 + q];
+            epilogue4<bf16_t, EPI>(CP, mrow + i * 32, ncol + j * 32 + r * 8, a, a, accumulate, save_pre);
           }
-          epilogue4<bf16_t, EPI>(CP, mrow + i * 32, ncol + j * 32 + r * 8, a, b, accumulate, save_pre);
+    } else {
+      // 16-bit outputs go through LDS so that global memory sees whole 128-byte lines: the wave works in
+      // units of 32 rows x 64 columns (two MFMA blocks), writes a unit into a 4 KiB slot in accumulator
+      // order (8 bytes per lane), reads it back row-wise (16 bytes per lane, 8 lanes per row) and stores.
+      // The two slots are the part of the retired stage buffer that only this wave's own loads refill, so
+      // no other wave is involved; LDS serves one wave's accesses in program order.
+      static_assert(NI % 2 == 0 && UPW >= 8, "staged epilogue: 64-column units, 8 KiB of stage per wave");
+      constexpr int NJP = NI / 2, NU = MI * NJP;
+      char* const slot0 = stages + ((g + 1) & 1) * STAGE + wave * UPW * 1024;
+      char* const slot1 = slot0 + 4096;
+      const int er = lane & 31, esw = (er >> 1) & 7;
+      const int rrow = lane >> 3, rchunk = lane & 7;
+      auto acc_pos = [&](char* slot, int jj, int r) -> bf16x4* {  // 4 columns of accumulator group (jj, r)
+        return reinterpret_cast<bf16x4*>(slot + er * 128 + (((jj * 4 + r) ^ esw) << 4) + khalf * 8);
+      };
+      auto row_pos = [&](char* slot, int it) -> bf16x8* {  // chunk rchunk of row 8 * it + rrow
+        const int rr = it * 8 + rrow;
+        return reinterpret_cast<bf16x8*>(slot + rr * 128 + ((rchunk ^ ((rr >> 1) & 7)) << 4));
+      };
+      auto unit_m = [&](int u) { return cc.m0 + wm * WM + (u / NJP) * 32; };
+      auto unit_n = [&](int u) { return cc.n0 + wn * WN + (u % NJP) * 64; };
+      // element offset of this lane's row-wise chunk of unit u, or -1 outside the matrix
+      auto row_off = [&](int u, int it) -> long {
+        const int m = unit_m(u) + it * 8 + rrow, n = unit_n(u) + rchunk * 8;
+        return (m < CP.M && n < CP.N) ? (long)m * CP.ldc + n : -1;
+      };
+      auto put_unit = [&](char* slot, const f32x16& c0, const f32x16& c1) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const f32x16& c = jj ? c1 : c0;
+            bf16x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = (bf16_t)c[r * 4 + q];
+            *acc_pos(slot, jj, r) = v;
+          }
+      };
+      auto store_unit = [&](char* slot, int u, void* C) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const bf16x8 v = *row_pos(slot, it);
+          const long o = row_off(u, it);
+          if (o >= 0) global_store16(static_cast<bf16_t*>(C) + o, v);
         }
+      };
+      if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          if (unit_m(u) >= CP.M) continue;
+          char* slot = (u & 1) ? slot1 : slot0;
+          put_unit(slot, acc[0][u / NJP][2 * (u % NJP)], acc[0][u / NJP][2 * (u % NJP) + 1]);
+          store_unit(slot, u, CP.C);
+        }
+      } else if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          if (unit_m(u) >= CP.M) continue;
+          const int i = u / NJP, j0 = 2 * (u % NJP);
+          f32x16 h0, h1;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            h0[r] = silu_f(acc[0][i][j0][r]) * acc[1][i][j0][r];
+            h1[r] = silu_f(acc[0][i][j0 + 1][r]) * acc[1][i][j0 + 1][r];
+          }
+          put_unit(slot0, h0, h1);
+          if (save_pre) put_unit(slot1, acc[0][i][j0], acc[0][i][j0 + 1]);
+          store_unit(slot0, u, CP.C);
+          if (save_pre) {
+            store_unit(slot1, u, CP.C2);
+            put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
+            store_unit(slot0, u, CP.C3);
+          }
+        }
+      } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+        // a and b of the unit come in row-wise (whole lines), one unit ahead of the arithmetic; da and db
+        // replace them in the slots at the positions the same lane read
+        bf16x8 pa[4], pb[4];
+        auto fetch = [&](int u) {
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {
+            const long o = row_off(u, it);
+            pa[it] = bf16x8{};
+            pb[it] = bf16x8{};
+            if (o >= 0) {
+              pa[it] = global_load16(static_cast<const bf16_t*>(CP.E1) + o);
+              pb[it] = global_load16(static_cast<const bf16_t*>(CP.E2) + o);
+            }
+          }
+        };
+        fetch(0);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          const int i = u / NJP, j0 = 2 * (u % NJP);
+          const bool active = unit_m(u) < CP.M;
+          if (active) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+              *row_pos(slot0, it) = pa[it];
+              *row_pos(slot1, it) = pb[it];
+            }
+          }
+          if (u + 1 < NU) fetch(u + 1);
+          if (active) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const bf16x4 av = *acc_pos(slot0, jj, r), bv = *acc_pos(slot1, jj, r);
+                bf16x4 da, db;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                  const float dh = acc[0][i][j0 + jj][r * 4 + q], a = (float)av[q], b = (float)bv[q];
+                  const float sig = 1.f / (1.f + __expf(-a));
+                  da[q] = (bf16_t)(dh * b * sig * (1.f + a * (1.f - sig)));
+                  db[q] = (bf16_t)(dh * a * sig);
+                }
+                *acc_pos(slot0, jj, r) = da;
+                *acc_pos(slot1, jj, r) = db;
+              }
+            store_unit(slot0, u, CP.C);
+            store_unit(slot1, u, CP.C2);
+          }
+        }
+      }
+    }
     cc.tile += G;
     open_tile(cc, CP);
   }
