@@ -56,6 +56,10 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
+// logistic function with the hardware reciprocal (1 ulp) instead of an IEEE division: the results are
+// rounded to bf16 anyway
+__device__ __forceinline__ float sigmoid_fast(float a) { return __builtin_amdgcn_rcpf(1.f + __expf(-a)); }
+
 #ifndef MODSE_DMA_SPREAD
 #define MODSE_DMA_SPREAD 2  // the stage loads of a step are issued in this many slices, between the MFMA groups
 #endif
@@ -79,7 +83,8 @@ struct Bf16Tile {
 
 // Walks the K steps of this workgroup's tiles in order.
 struct StepCursor {
-  int tile, step, nsteps, nk;
+  const GemmProblem* gp;  // the tile's problem (read field by field: a copy of the struct would live in scratch)
+  int tile, step, nsteps, nk, K;
   int m0, n0;
   bool valid;
 };
@@ -120,37 +125,54 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   const bool loads_a = wave * UPW < UA;                       // wave-uniform: which operand this wave loads
   const bool loads_t = loads_a ? A_T : B_T;                   // ... and whether it is a transposed one
 
-  auto open_tile = [&](StepCursor& c, GemmProblem& Q) {
+  auto open_tile = [&](StepCursor& c) {
     TileCoord tc;
     c.valid = c.tile < total && decode_tile(plan, c.tile, tc);
     if (!c.valid) return;
-    Q = plan->prob[tc.p];
+    c.gp = plan->prob + tc.p;
     c.m0 = tc.mt * BM;
     c.n0 = tc.nt * BN;
     c.step = 0;
-    c.nk = (Q.K + BK - 1) / BK;
+    c.K = c.gp->K;
+    c.nk = (c.K + BK - 1) / BK;
     c.nsteps = (EPI == EPI_STORE_DUALK) ? 2 * c.nk : c.nk;
   };
 
   // ---- issue side: runs one K step ahead of the MFMAs, across tile boundaries
   StepCursor ic;
-  GemmProblem IP;
+  const char* ibase[2] = {nullptr, nullptr};  // operand this wave loads from, per pass of a dual-K product
+  int ikstride = 1;                           // elements between consecutive K of that operand
   uint32_t ioff[UPW];  // byte offset of this lane's chunk per load unit (K offset 0) from the operand base
   // tiles without K steps (an expert that received no token, in a weight-gradient GEMM) take no stage
   auto skip_empty = [&]() {
     while (ic.valid && ic.nsteps == 0) {
       ic.tile += G;
-      open_tile(ic, IP);
+      open_tile(ic);
     }
   };
   auto issue_offsets = [&]() {
+    const GemmProblem* P = ic.gp;
+    {  // operand this wave loads from (wave-uniform)
+      const int u = wave * UPW;
+      if (u < UA) {
+        ibase[0] = static_cast<const char*>(P->A);
+        ibase[1] = static_cast<const char*>(P->A2);
+      } else if (NB == 2) {
+        ibase[0] = ibase[1] = static_cast<const char*>((u - UA) * 8 >= BN ? P->B2 : P->B);
+      } else {
+        ibase[0] = static_cast<const char*>(P->B);
+        ibase[1] = static_cast<const char*>(P->B2);
+      }
+    }
+    const int PM = P->M, PN = P->N, lda = P->lda, ldb = P->ldb;
+    ikstride = loads_t ? (loads_a ? lda : ldb) : 1;
     if (loads_t) {  // unit = K rows 2u, 2u+1; LDS position (k, p) holds 16-byte chunk p ^ (4 * (k & 3))
 #pragma unroll
       for (int i = 0; i < UPW; ++i) {
         const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
         const int k = 2 * ul + t_row;
         const int c16 = t_chunk ^ (4 * (k & 3));
-        const int x0 = loads_a ? ic.m0 : ic.n0, X = loads_a ? IP.M : IP.N, ld = loads_a ? IP.lda : IP.ldb;
+        const int x0 = loads_a ? ic.m0 : ic.n0, X = loads_a ? PM : PN, ld = loads_a ? lda : ldb;
         ioff[i] = (uint32_t)(k * ld + min(x0 + c16 * 8, X - 8)) * 2u;  // columns past the end repeat the last chunk
       }
       return;
@@ -160,19 +182,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       const int u = wave * UPW + i;
       const int lchunk = (i & 1) ? lchunk_odd : lchunk_even;  // UPW is even: unit parity = i parity
       if (u < UA) {
-        ioff[i] = (uint32_t)(min(ic.m0 + u * 8 + lrow, IP.M - 1) * IP.lda + lchunk) * 2u;
+        ioff[i] = (uint32_t)(min(ic.m0 + u * 8 + lrow, PM - 1) * lda + lchunk) * 2u;
       } else {
         const int r = ((u - UA) * 8 + lrow) % BN;
-        ioff[i] = (uint32_t)(min(ic.n0 + r, IP.N - 1) * IP.ldb + lchunk) * 2u;
+        ioff[i] = (uint32_t)(min(ic.n0 + r, PN - 1) * ldb + lchunk) * 2u;
       }
     }
-  };
-  // operand this wave loads from (wave-uniform)
-  auto my_operand = [&](int pass) -> const char* {
-    const int u = wave * UPW;
-    if (u < UA) return static_cast<const char*>(pass ? IP.A2 : IP.A);
-    if (NB == 2) return static_cast<const char*>((u - UA) * 8 >= BN ? IP.B2 : IP.B);
-    return static_cast<const char*>(pass ? IP.B2 : IP.B);
   };
   // issue load units [first, first + count) of the issue cursor's step into stage buffer `buf`
   auto issue_slice = [&](int buf, int first, int count) {
@@ -180,9 +195,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     const int pass = (EPI == EPI_STORE_DUALK && ic.step >= ic.nk) ? 1 : 0;
     const int k0 = (ic.step - pass * ic.nk) * BK;
     const uint32_t dst = lds_mine + buf * STAGE;
-    const int kstride = loads_t ? (loads_a ? IP.lda : IP.ldb) : 1;  // elements between consecutive K
-    const char* base = my_operand(pass) + (size_t)k0 * kstride * 2;
-    if (k0 + BK <= IP.K) {
+    const char* base = ibase[pass] + (size_t)k0 * ikstride * 2;
+    if (k0 + BK <= ic.K) {
 #pragma unroll
       for (int i = first; i < first + count; ++i) dma_b128_s(base, ioff[i], dst + i * 1024);
     } else if (loads_t) {  // partial last step: K rows beyond K read zeros
@@ -190,14 +204,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       for (int i = first; i < first + count; ++i) {
         const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
         const char* src = base + ioff[i];
-        if (k0 + 2 * ul + t_row >= IP.K) src = reinterpret_cast<const char*>(g_zero_chunk);
+        if (k0 + 2 * ul + t_row >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
         dma_b128(src, dst + i * 1024);
       }
     } else {  // last step of a pass when K % 64 != 0: chunks beyond K read zeros
 #pragma unroll
       for (int i = first; i < first + count; ++i) {
         const char* src = base + ioff[i];
-        if (k0 + ((i & 1) ? lchunk_odd : lchunk_even) >= IP.K) src = reinterpret_cast<const char*>(g_zero_chunk);
+        if (k0 + ((i & 1) ? lchunk_odd : lchunk_even) >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
         dma_b128(src, dst + i * 1024);
       }
     }
@@ -206,7 +220,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     if (!ic.valid) return;
     if (++ic.step >= ic.nsteps) {
       ic.tile += G;
-      open_tile(ic, IP);
+      open_tile(ic);
       skip_empty();
       if (ic.valid) issue_offsets();
     }
@@ -214,12 +228,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 
   // ---- compute side
   StepCursor cc;
-  GemmProblem CP;
   cc.tile = first_tile_of_block();
-  open_tile(cc, CP);
+  open_tile(cc);
   if (!cc.valid) return;
   ic = cc;
-  IP = CP;
   skip_empty();
   if (ic.valid) issue_offsets();
   const bool any_stage = ic.valid;
@@ -333,6 +345,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     }
 
     // ---- epilogue.  For register group r of block (i, j) the lane holds columns n .. n+3 of row m.
+    const GemmProblem& CP = *cc.gp;
+    const int cM = CP.M, cN = CP.N, cld = CP.ldc;
     if constexpr (EPI == EPI_STORE_F32) {
       const int mrow = cc.m0 + wm * WM + (lane & 31);
       const int ncol = cc.n0 + wn * WN + 4 * khalf;
@@ -371,7 +385,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       // element offset of this lane's row-wise chunk of unit u, or -1 outside the matrix
       auto row_off = [&](int u, int it) -> long {
         const int m = unit_m(u) + it * 8 + rrow, n = unit_n(u) + rchunk * 8;
-        return (m < CP.M && n < CP.N) ? (long)m * CP.ldc + n : -1;
+        return (m < cM && n < cN) ? (long)m * cld + n : -1;
       };
       auto put_unit = [&](char* slot, const f32x16& c0, const f32x16& c1) {
 #pragma unroll
@@ -396,7 +410,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
-          if (unit_m(u) >= CP.M) continue;
+          if (unit_m(u) >= cM) continue;
           char* slot = (u & 1) ? slot1 : slot0;
           put_unit(slot, acc[0][u / NJP][2 * (u % NJP)], acc[0][u / NJP][2 * (u % NJP) + 1]);
           store_unit(slot, u, CP.C);
@@ -404,13 +418,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
-          if (unit_m(u) >= CP.M) continue;
+          if (unit_m(u) >= cM) continue;
           const int i = u / NJP, j0 = 2 * (u % NJP);
           f32x16 h0, h1;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            h0[r] = silu_f(acc[0][i][j0][r]) * acc[1][i][j0][r];
-            h1[r] = silu_f(acc[0][i][j0 + 1][r]) * acc[1][i][j0 + 1][r];
+            h0[r] = acc[0][i][j0][r] * sigmoid_fast(acc[0][i][j0][r]) * acc[1][i][j0][r];
+            h1[r] = acc[0][i][j0 + 1][r] * sigmoid_fast(acc[0][i][j0 + 1][r]) * acc[1][i][j0 + 1][r];
           }
           put_unit(slot0, h0, h1);
           if (save_pre) put_unit(slot1, acc[0][i][j0], acc[0][i][j0 + 1]);
@@ -441,7 +455,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
           const int i = u / NJP, j0 = 2 * (u % NJP);
-          const bool active = unit_m(u) < CP.M;
+          const bool active = unit_m(u) < cM;
           if (active) {
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
@@ -460,7 +474,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                   const float dh = acc[0][i][j0 + jj][r * 4 + q], a = (float)av[q], b = (float)bv[q];
-                  const float sig = 1.f / (1.f + __expf(-a));
+                  const float sig = sigmoid_fast(a);
                   da[q] = (bf16_t)(dh * b * sig * (1.f + a * (1.f - sig)));
                   db[q] = (bf16_t)(dh * a * sig);
                 }
@@ -474,7 +488,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       }
     }
     cc.tile += G;
-    open_tile(cc, CP);
+    open_tile(cc);
   }
   // drain: nothing may still be writing LDS when the workgroup's allocation is released
   __builtin_amdgcn_s_waitcnt(0x0070);
