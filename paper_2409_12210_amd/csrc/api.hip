@@ -110,7 +110,7 @@ SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
 }
 
 struct BwdLayout {
-  size_t plan[5], Xp, dO, dA, dB, dXp, dg, dWg_partial, total;
+  size_t plan[3], Xp, dO, dA, dB, dXp, dg, dWg_partial, total;
 };
 
 BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
@@ -119,7 +119,7 @@ BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
   const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k;
   const size_t h = hidden_elems_max(L) * es;
   const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
-  for (int i = 0; i < 5; ++i) w.plan[i] = c.take(sizeof(GemmPlan));
+  for (int i = 0; i < 3; ++i) w.plan[i] = c.take(sizeof(GemmPlan));
   w.Xp = c.take(Tk * L.d * es);
   w.dO = c.take(Tk * L.d * es);
   w.dA = c.take(h);
@@ -326,9 +326,7 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
   pa.dW1 = dW1; pa.dW3 = dW3; pa.dW2 = dW2;
   pa.dh = reinterpret_cast<GemmPlan*>(wsb + w.plan[0]);
   pa.dx = reinterpret_cast<GemmPlan*>(wsb + w.plan[1]);
-  pa.wg1 = reinterpret_cast<GemmPlan*>(wsb + w.plan[2]);
-  pa.wg3 = reinterpret_cast<GemmPlan*>(wsb + w.plan[3]);
-  pa.wg2 = reinterpret_cast<GemmPlan*>(wsb + w.plan[4]);
+  pa.wg = reinterpret_cast<GemmPlan*>(wsb + w.plan[2]);
   pa.dh_tile = gemm_tile_shape(dt, EPI_SWIGLU_BWD, T);
   pa.dx_tile = gemm_tile_shape(dt, EPI_STORE_DUALK, T);
   pa.wg_tile = gemm_tile_shape(dt, EPI_STORE_F32, T);
@@ -342,9 +340,7 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
   int64_t fmax = L.f[L.order[0]];
   const int64_t wg13 = tiles_bound(L, fmax, pa.wg_tile, false);
   const int64_t wg2 = tiles_bound(L, L.d, pa.wg_tile, true);
-  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg1, accumulate, 0, wg13, s));
-  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg3, accumulate, 0, wg13, s));
-  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg2, accumulate, 0, wg2, s));
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg, accumulate, 0, 2 * wg13 + wg2, s));
   stamp.mark(MODSE_STAGE_BWD_WGRAD);
 
   HIP_TRY(launch_bwd_router(L, dt, x, W_gate, pa.dXp, dg, R, dX, reinterpret_cast<float*>(wsb + w.dWg_partial),

@@ -6,6 +6,7 @@
 #include "modse.h"
 
 #define MODSE_MAX_EXPERTS 64
+#define MODSE_MAX_PROBLEMS (3 * MODSE_MAX_EXPERTS)  // the three weight-gradient GEMMs share one launch
 #define MODSE_ROUTE_TOKENS_PER_BLOCK 32  // tokens handled by one block of the router / scatter kernels
 
 typedef __bf16 bf16_t;
@@ -80,8 +81,8 @@ struct GemmProblem {
 };
 
 struct GemmPlan {
-  GemmProblem prob[MODSE_MAX_EXPERTS];
-  int32_t tile_start[MODSE_MAX_EXPERTS + 1];  // prefix sum of mtiles*ntiles in problem order
+  GemmProblem prob[MODSE_MAX_PROBLEMS];
+  int32_t tile_start[MODSE_MAX_PROBLEMS + 1];  // prefix sum of mtiles*ntiles in problem order
   int32_t n_prob;
   int32_t pad[2];
 };
@@ -155,7 +156,7 @@ struct BwdPlanArgs {
   const void *W1, *W3, *W2;
   void *dA, *dB, *dXp;
   float *dW1, *dW3, *dW2;
-  GemmPlan *dh, *dx, *wg1, *wg3, *wg2;
+  GemmPlan *dh, *dx, *wg;  // wg: dW1, dW3 and dW2 of every expert in one problem list
   TileShape dh_tile, dx_tile, wg_tile;
 };
 hipError_t launch_plan_bwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,

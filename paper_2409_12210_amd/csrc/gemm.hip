@@ -95,12 +95,14 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GemmPlan* __restrict_
 // ------------------------------------------------------------------------------------------------
 // plan kernels (single block): device-side counts -> problem tables
 // ------------------------------------------------------------------------------------------------
-__device__ inline void finish_plan(GemmPlan* plan, int i, bool on, int n, int bm, int bn, int* s_tiles) {
-  if (on) {
-    GemmProblem& P = plan->prob[i];
+// Every thread has written its problems (n in total); fills in the tile counts and the tile prefix.
+__device__ inline void finish_plan(GemmPlan* plan, int i, int n, int bm, int bn, int* s_tiles) {
+  __syncthreads();
+  for (int q = i; q < n; q += blockDim.x) {
+    GemmProblem& P = plan->prob[q];
     P.mtiles = (P.M + bm - 1) / bm;
     P.ntiles = (P.N + bn - 1) / bn;
-    s_tiles[i] = P.mtiles * P.ntiles;
+    s_tiles[q] = P.mtiles * P.ntiles;
   }
   __syncthreads();
   if (i == 0) {
@@ -120,7 +122,7 @@ __device__ inline char* vadd(void* p, size_t bytes) { return p ? static_cast<cha
 
 __global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
                                                       const int32_t* __restrict__ offsets, FwdPlanArgs a) {
-  __shared__ int s_tiles[MODSE_MAX_EXPERTS];
+  __shared__ int s_tiles[MODSE_MAX_PROBLEMS];
   const int i = threadIdx.x;
   const bool on = i < L.N;
   const int e = on ? L.order[i] : 0;
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, co
     P.lda = d; P.ldb = d; P.ldc = f;
     a.up->prob[i] = P;
   }
-  finish_plan(a.up, i, on, L.N, a.up_tile.bm, a.up_tile.bn, s_tiles);
+  finish_plan(a.up, i, L.N, a.up_tile.bm, a.up_tile.bn, s_tiles);
   if (on) {
     GemmProblem P = {};
     P.A = cadd(a.H, hoff * es);
@@ -150,12 +152,12 @@ __global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, co
     P.lda = f; P.ldb = f; P.ldc = d;
     a.down->prob[i] = P;
   }
-  finish_plan(a.down, i, on, L.N, a.down_tile.bm, a.down_tile.bn, s_tiles);
+  finish_plan(a.down, i, L.N, a.down_tile.bm, a.down_tile.bn, s_tiles);
 }
 
 __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
                                                       const int32_t* __restrict__ offsets, BwdPlanArgs a) {
-  __shared__ int s_tiles[MODSE_MAX_EXPERTS];
+  __shared__ int s_tiles[MODSE_MAX_PROBLEMS];
   const int i = threadIdx.x;
   const bool on = i < L.N;
   const int e = on ? L.order[i] : 0;
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
     P.lda = d; P.ldb = f; P.ldc = f;
     a.dh->prob[i] = P;
   }
-  finish_plan(a.dh, i, on, L.N, a.dh_tile.bm, a.dh_tile.bn, s_tiles);
+  finish_plan(a.dh, i, L.N, a.dh_tile.bm, a.dh_tile.bn, s_tiles);
   if (on) {  // dXp = dA W1 + dB W3 (W1_e, W3_e are [f, d]: [K, N] operands)
     GemmProblem P = {};
     P.A = cadd(a.dA, hoff * es);
@@ -189,29 +191,30 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
     P.lda = f; P.ldb = d; P.ldc = d;
     a.dx->prob[i] = P;
   }
-  finish_plan(a.dx, i, on, L.N, a.dx_tile.bm, a.dx_tile.bn, s_tiles);
-  for (int which = 0; which < 2; ++which) {  // dW1 = dA^T Xp, dW3 = dB^T Xp: contraction over the expert's tokens
-    if (on) {
+  finish_plan(a.dx, i, L.N, a.dx_tile.bm, a.dx_tile.bn, s_tiles);
+  // Weight gradients contract over the expert's tokens, so a tile costs n_e K-steps whatever its expert's
+  // width: the three GEMMs of one expert are listed together, experts by falling token count.
+  if (on) {
+    int rank = 0;
+    for (int q = 0; q < L.N; ++q) rank += (counts[q] > n_e || (counts[q] == n_e && q < e)) ? 1 : 0;
+    for (int which = 0; which < 2; ++which) {  // dW1 = dA^T Xp, dW3 = dB^T Xp
       GemmProblem P = {};
       P.A = cadd(which ? a.dB : a.dA, hoff * es);  // [K = n_e, M = f]
       P.B = cadd(a.Xp, roff * es);                  // [K = n_e, N = d]
       P.C = (which ? a.dW3 : a.dW1) + woff;
       P.M = f; P.N = d; P.K = n_e;
       P.lda = f; P.ldb = d; P.ldc = d;
-      (which ? a.wg3 : a.wg1)->prob[i] = P;
+      a.wg->prob[3 * rank + which] = P;
     }
-    finish_plan(which ? a.wg3 : a.wg1, i, on, L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
-  }
-  if (on) {  // dW2 = dO^T H
-    GemmProblem P = {};
+    GemmProblem P = {};  // dW2 = dO^T H
     P.A = cadd(a.dO, roff * es);  // [K = n_e, M = d]
     P.B = cadd(a.H, hoff * es);   // [K = n_e, N = f]
     P.C = a.dW2 + woff;
     P.M = d; P.N = f; P.K = n_e;
     P.lda = d; P.ldb = f; P.ldc = f;
-    a.wg2->prob[i] = P;
+    a.wg->prob[3 * rank + 2] = P;
   }
-  finish_plan(a.wg2, i, on, L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
+  finish_plan(a.wg, i, 3 * L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
 }
 
 int num_cus() {

@@ -84,7 +84,7 @@ struct Bf16Tile {
 // Walks the K steps of this workgroup's tiles in order.
 struct StepCursor {
   const GemmProblem* gp;  // the tile's problem (read field by field: a copy of the struct would live in scratch)
-  int tile, step, nsteps, nk, K;
+  int tile, round, step, nsteps, nk, K;
   int m0, n0;
   bool valid;
 };
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int total = plan->tile_start[plan->n_prob];
-  const int G = gridDim.x;
+  const int first_tile = first_tile_of_block();
   const uint32_t lds_mine = __builtin_amdgcn_readfirstlane(lds_address(stages)) + wave * UPW * 1024;
   const int lrow = lane >> 3;  // row inside a load unit
   // element offset of the chunk this lane fetches, for even and odd load units: LDS position (row, p)
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   // tiles without K steps (an expert that received no token, in a weight-gradient GEMM) take no stage
   auto skip_empty = [&]() {
     while (ic.valid && ic.nsteps == 0) {
-      ic.tile += G;
+      ic.tile = tile_of_round(first_tile, ++ic.round);
       open_tile(ic);
     }
   };
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   auto advance_issue = [&]() {
     if (!ic.valid) return;
     if (++ic.step >= ic.nsteps) {
-      ic.tile += G;
+      ic.tile = tile_of_round(first_tile, ++ic.round);
       open_tile(ic);
       skip_empty();
       if (ic.valid) issue_offsets();
@@ -228,7 +228,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 
   // ---- compute side
   StepCursor cc;
-  cc.tile = first_tile_of_block();
+  cc.tile = first_tile;
+  cc.round = 0;
   open_tile(cc);
   if (!cc.valid) return;
   ic = cc;
@@ -487,7 +488,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         }
       }
     }
-    cc.tile += G;
+    cc.tile = tile_of_round(first_tile, ++cc.round);
     open_tile(cc);
   }
   // drain: nothing may still be writing LDS when the workgroup's allocation is released

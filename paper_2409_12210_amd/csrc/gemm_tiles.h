@@ -13,9 +13,14 @@ struct TileCoord {
 
 __device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, TileCoord& tc) {
   const int np = plan->n_prob;
-  int p = 0;
-  while (p < np && tile >= plan->tile_start[p + 1]) ++p;
-  if (p >= np) return false;
+  if (tile >= plan->tile_start[np]) return false;
+  int lo = 0, hi = np;  // last p with tile_start[p] <= tile (problems without tiles are stepped over)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (plan->tile_start[mid] <= tile) lo = mid;
+    else hi = mid;
+  }
+  const int p = lo;
   const int local = tile - plan->tile_start[p];
   const int mtiles = plan->prob[p].mtiles, ntiles = plan->prob[p].ntiles;
   const int per_group = GROUP_M * ntiles;
@@ -33,6 +38,14 @@ __device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, 
 __device__ inline int first_tile_of_block() {
   const int G = gridDim.x, b = blockIdx.x;
   return (G % NUM_XCD == 0) ? (b % NUM_XCD) * (G / NUM_XCD) + b / NUM_XCD : b;
+}
+
+// Tile of a workgroup in round r: the rounds deal the list out alternately forwards and backwards.  With
+// the problems sorted by falling cost per tile this keeps the workgroups' sums close (a plain round-robin
+// hands the same workgroups the dearest tile of every round).
+__device__ inline int tile_of_round(int first, int r) {
+  const int G = gridDim.x;
+  return r * G + ((r & 1) ? G - 1 - first : first);
 }
 
 __device__ inline float silu_f(float a) { return a / (1.f + __expf(-a)); }
