@@ -94,15 +94,15 @@ FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
 }
 
 struct SavedLayout {
-  size_t Apre, Bpre, H, O, total;
+  size_t dHdA, dHdB, H, O, total;
 };
 
 SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
   SavedLayout s;
   Carver c;
   const size_t es = esize_of(dt), h = hidden_elems_max(L) * es;
-  s.Apre = c.take(h);
-  s.Bpre = c.take(h);
+  s.dHdA = c.take(h);
+  s.dHdB = c.take(h);
   s.H = c.take(h);
   s.O = c.take((size_t)L.T * L.k * L.d * es);
   s.total = c.off;
@@ -271,7 +271,7 @@ modse_status modse_layer_fwd(const modse_desc* desc, int64_t T, const void* x, c
   if (saved) {
     const SavedLayout sl = saved_layout(L, dt);
     char* sb = static_cast<char*>(saved);
-    pa.Apre = sb + sl.Apre; pa.Bpre = sb + sl.Bpre; pa.H = sb + sl.H; pa.O = sb + sl.O;
+    pa.dHdA = sb + sl.dHdA; pa.dHdB = sb + sl.dHdB; pa.H = sb + sl.H; pa.O = sb + sl.O;
   } else {
     pa.H = wsb + w.H; pa.O = wsb + w.O;
   }
@@ -320,7 +320,7 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
   HIP_TRY(launch_bwd_prep(L, dt, dY, sb + sl.O, R, dO, dg, s));
   BwdPlanArgs pa;
   std::memset(&pa, 0, sizeof(pa));
-  pa.Xp = Xp; pa.dO = dO; pa.H = sb + sl.H; pa.Apre = sb + sl.Apre; pa.Bpre = sb + sl.Bpre;
+  pa.Xp = Xp; pa.dO = dO; pa.H = sb + sl.H; pa.dHdA = sb + sl.dHdA; pa.dHdB = sb + sl.dHdB;
   pa.W1 = W1; pa.W3 = W3; pa.W2 = W2;
   pa.dA = wsb + w.dA; pa.dB = wsb + w.dB; pa.dXp = wsb + w.dXp;
   pa.dW1 = dW1; pa.dW3 = dW3; pa.dW2 = dW2;

@@ -90,8 +90,8 @@ struct GemmPlan {
 enum GemmEpilogue {
   EPI_STORE = 0,       // C = acc (element type of the layer)
   EPI_STORE_F32 = 1,   // C = acc or C += acc, float32 (weight gradients)
-  EPI_SWIGLU = 2,      // two accumulators a, b: C = silu(a)*b; optionally C2 = a, C3 = b
-  EPI_SWIGLU_BWD = 3,  // acc = dh; E1 = a, E2 = b: C = da, C2 = db
+  EPI_SWIGLU = 2,      // two accumulators a, b: C = h = silu(a)*b; optionally C2 = dh/da, C3 = dh/db
+  EPI_SWIGLU_BWD = 3,  // acc = dh; E1 = dh/da, E2 = dh/db (saved by the forward pass): C = da, C2 = db
   EPI_STORE_DUALK = 4, // C = acc over two operand pairs (A,B) and (A2,B2)
 };
 
@@ -144,7 +144,7 @@ hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* pla
 
 struct FwdPlanArgs {
   const void *Xp, *W1, *W3, *W2;
-  void *H, *Apre, *Bpre, *O;  // Apre/Bpre may be null
+  void *H, *dHdA, *dHdB, *O;  // dHdA/dHdB (derivatives of h by the two pre-activations) may be null
   GemmPlan *up, *down;
   TileShape up_tile, down_tile;
 };
@@ -152,7 +152,7 @@ hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* co
                            const FwdPlanArgs& a, hipStream_t s);
 
 struct BwdPlanArgs {
-  const void *Xp, *dO, *H, *Apre, *Bpre;
+  const void *Xp, *dO, *H, *dHdA, *dHdB;
   const void *W1, *W3, *W2;
   void *dA, *dB, *dXp;
   float *dW1, *dW3, *dW2;

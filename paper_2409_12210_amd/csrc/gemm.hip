@@ -136,8 +136,8 @@ __global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, co
     P.B = cadd(a.W1, (size_t)L.foff[e] * d * es);
     P.B2 = cadd(a.W3, (size_t)L.foff[e] * d * es);
     P.C = vadd(a.H, hoff * es);
-    P.C2 = vadd(a.Apre, hoff * es);
-    P.C3 = vadd(a.Bpre, hoff * es);
+    P.C2 = vadd(a.dHdA, hoff * es);
+    P.C3 = vadd(a.dHdB, hoff * es);
     P.M = n_e; P.N = f; P.K = d;
     P.lda = d; P.ldb = d; P.ldc = f;
     a.up->prob[i] = P;
@@ -173,8 +173,8 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
     P.B = cadd(a.W2, woff * es);
     P.C = vadd(a.dA, hoff * es);
     P.C2 = vadd(a.dB, hoff * es);
-    P.E1 = cadd(a.Apre, hoff * es);
-    P.E2 = cadd(a.Bpre, hoff * es);
+    P.E1 = cadd(a.dHdA, hoff * es);
+    P.E2 = cadd(a.dHdB, hoff * es);
     P.M = n_e; P.N = f; P.K = d;
     P.lda = d; P.ldb = f; P.ldc = f;
     a.dh->prob[i] = P;

@@ -388,17 +388,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         const int m = unit_m(u) + it * 8 + rrow, n = unit_n(u) + rchunk * 8;
         return (m < cM && n < cN) ? (long)m * cld + n : -1;
       };
+      auto put_block = [&](char* slot, int jj, const f32x16& c) {  // one 32 x 32 block of the unit
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          bf16x4 v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = (bf16_t)c[r * 4 + q];
+          *acc_pos(slot, jj, r) = v;
+        }
+      };
       auto put_unit = [&](char* slot, const f32x16& c0, const f32x16& c1) {
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const f32x16& c = jj ? c1 : c0;
-            bf16x4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = (bf16_t)c[r * 4 + q];
-            *acc_pos(slot, jj, r) = v;
-          }
+        put_block(slot, 0, c0);
+        put_block(slot, 1, c1);
       };
       auto store_unit = [&](char* slot, int u, void* C) {
 #pragma unroll
@@ -421,14 +422,25 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         for (int u = 0; u < NU; ++u) {
           if (unit_m(u) >= cM) continue;
           const int i = u / NJP, j0 = 2 * (u % NJP);
-          f32x16 h0, h1;
+          // h = silu(a) b and the saved term p = dh/da go to the slots four columns at a time; q = dh/db
+          // takes b's place in the accumulator and follows once the slot of h is free
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            h0[r] = acc[0][i][j0][r] * sigmoid_fast(acc[0][i][j0][r]) * acc[1][i][j0][r];
-            h1[r] = acc[0][i][j0 + 1][r] * sigmoid_fast(acc[0][i][j0 + 1][r]) * acc[1][i][j0 + 1][r];
-          }
-          put_unit(slot0, h0, h1);
-          if (save_pre) put_unit(slot1, acc[0][i][j0], acc[0][i][j0 + 1]);
+          for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              bf16x4 hv, pv;
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const float a = acc[0][i][j0 + jj][r * 4 + q4], b = acc[1][i][j0 + jj][r * 4 + q4];
+                float h, p, q;
+                swiglu_terms(a, b, sigmoid_fast(a), h, p, q);
+                hv[q4] = (bf16_t)h;
+                pv[q4] = (bf16_t)p;
+                acc[1][i][j0 + jj][r * 4 + q4] = q;
+              }
+              *acc_pos(slot0, jj, r) = hv;
+              if (save_pre) *acc_pos(slot1, jj, r) = pv;
+            }
           store_unit(slot0, u, CP.C);
           if (save_pre) {
             store_unit(slot1, u, CP.C2);
@@ -437,8 +449,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
           }
         }
       } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-        // a and b of the unit come in row-wise (whole lines), one unit ahead of the arithmetic; da and db
-        // replace them in the slots at the positions the same lane read
+        // the saved terms p = dh/da and q = dh/db of the unit come in row-wise (whole lines), one unit ahead
+        // of the arithmetic; da = dh p and db = dh q replace them in the slots at the positions the lane read
         bf16x8 pa[4], pb[4];
         auto fetch = [&](int u) {
 #pragma unroll
@@ -474,10 +486,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
                 bf16x4 da, db;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                  const float dh = acc[0][i][j0 + jj][r * 4 + q], a = (float)av[q], b = (float)bv[q];
-                  const float sig = sigmoid_fast(a);
-                  da[q] = (bf16_t)(dh * b * sig * (1.f + a * (1.f - sig)));
-                  db[q] = (bf16_t)(dh * a * sig);
+                  const float dh = acc[0][i][j0 + jj][r * 4 + q];
+                  da[q] = (bf16_t)(dh * (float)av[q]);
+                  db[q] = (bf16_t)(dh * (float)bv[q]);
                 }
                 *acc_pos(slot0, jj, r) = da;
                 *acc_pos(slot1, jj, r) = db;

@@ -50,6 +50,15 @@ __device__ inline int tile_of_round(int first, int r) {
 
 __device__ inline float silu_f(float a) { return a / (1.f + __expf(-a)); }
 
+// SwiGLU of the pre-activations a = <W1 row, x>, b = <W3 row, x> with sig = 1 / (1 + exp(-a)):
+//   h = silu(a) b,   p = dh/da = b sig (1 + a (1 - sig)),   q = dh/db = silu(a).
+// The forward pass saves p and q (not a and b), so the backward epilogue is two multiplications.
+__device__ inline void swiglu_terms(float a, float b, float sig, float& h, float& p, float& q) {
+  q = a * sig;
+  h = q * b;
+  p = b * sig * (1.f + a * (1.f - sig));
+}
+
 // Epilogue on 4 consecutive columns n..n+3 of row m.  a = first accumulator, b = second (SwiGLU only).
 template <typename T, int EPI>
 __device__ inline void epilogue4(const GemmProblem& P, int m, int n, const float a[4], const float b[4],
@@ -69,23 +78,22 @@ __device__ inline void epilogue4(const GemmProblem& P, int m, int n, const float
     }
     store4(c, v);
   } else if constexpr (EPI == EPI_SWIGLU) {
-    float h[4];
+    float h[4], p[4], q[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) h[i] = silu_f(a[i]) * b[i];
+    for (int i = 0; i < 4; ++i) swiglu_terms(a[i], b[i], 1.f / (1.f + __expf(-a[i])), h[i], p[i], q[i]);
     store4(static_cast<T*>(P.C) + o, h);
     if (save_pre) {
-      store4(static_cast<T*>(P.C2) + o, a);
-      store4(static_cast<T*>(P.C3) + o, b);
+      store4(static_cast<T*>(P.C2) + o, p);
+      store4(static_cast<T*>(P.C3) + o, q);
     }
   } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-    float av[4], bv[4], da[4], db[4];
-    load4(static_cast<const T*>(P.E1) + o, av);
-    load4(static_cast<const T*>(P.E2) + o, bv);
+    float p[4], q[4], da[4], db[4];
+    load4(static_cast<const T*>(P.E1) + o, p);
+    load4(static_cast<const T*>(P.E2) + o, q);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float sig = 1.f / (1.f + __expf(-av[i]));
-      da[i] = a[i] * bv[i] * sig * (1.f + av[i] * (1.f - sig));
-      db[i] = a[i] * av[i] * sig;
+      da[i] = a[i] * p[i];
+      db[i] = a[i] * q[i];
     }
     store4(static_cast<T*>(P.C) + o, da);
     store4(static_cast<T*>(P.C2) + o, db);
