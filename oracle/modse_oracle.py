@@ -15,6 +15,12 @@ What it follows:
                        switched off, see readings below)
   * experts            E_i has its own hidden width h_i     (Sec. 3.1)
   * pair constraint    h_{i1} + h_{i2} = 2h per pair        (Sec. 3.1)
+  * noise term         RMSNorm(Softplus(x W_n)) added to the logits (second
+                       term of H(x), Sec. 2 Eq. 4-5) -- optional, see readings
+  * auxiliary loss     L_a = alpha N sum_i f_i P_i          (Sec. 3.2 Eq. 9-12)
+  * routing statistics per-slot token counts per expert, their max/min ratio
+                       (Appendix A tables) and the average hidden width of the
+                       chosen experts (Sec. 4.3, workload measure)
 
 Readings where the paper is silent or garbled (all listed in the design notes):
   * W_g is d_model x N (the paper prints h_input x h; a gate needs one logit
@@ -27,6 +33,15 @@ Readings where the paper is silent or garbled (all listed in the design notes):
   * The gate weight multiplies the expert OUTPUT (Eq. 1), in full precision.
   * Backward is the chain rule through the above; KeepTopK is piecewise
     constant, so logits that were not kept get zero gradient.
+  * Noise term (off unless asked for): the text says it is added to the expert
+    outputs, the formula adds it to the logits; the formula is followed.  It
+    carries no random factor, so it is a deterministic function of x.  RMSNorm
+    runs over the N per-expert values of one token (n = N), gamma is one
+    scalar, epsilon is a parameter (1e-6 in the tests).
+  * Auxiliary loss: p(x) is the softmax of H(x) over ALL N experts (the gate of
+    Eq. 2 is a softmax over the kept ones only); "routed to expert i" in f_i
+    means argmax p(x) = i, the first choice, ties to the lower index; f_i is a
+    constant in the backward pass (it is piecewise constant in the logits).
 
 Every function works in float64 on whatever values it is given (bf16 configs
 pass bf16-representable numbers, which fp64 holds exactly); there is no
@@ -83,11 +98,36 @@ def expert_weights(W1, W3, W2, d_ff, d_model, e):
 # --------------------------------------------------------------------------
 # router and gate  (Sec. 2 Eq. 2, Eq. 3)
 # --------------------------------------------------------------------------
-def router_logits(x, W_gate, logit_bias=None):
-    """H(x) = x W_g (+ bias)."""
+def softplus(u):
+    """log(1 + exp(u))  (Sec. 2 Eq. 5)."""
+    return np.logaddexp(0.0, np.asarray(u, dtype=F64))
+
+
+@dataclass
+class Noise:
+    """Parameters of the second term of H(x): W_n [d, N], the RMSNorm gain gamma and epsilon (Sec. 2)."""
+    W_noise: np.ndarray
+    gamma: float
+    eps: float = 1e-6
+
+
+def noise_term(x, noise: "Noise"):
+    """RMSNorm(Softplus(x W_n)) per token, the norm taken over the N per-expert values  (Sec. 2, second term
+    of the H(x) equation with Eq. 4 and Eq. 5).  Returns (z, u, s, r): the term, x W_n, its softplus and the
+    root-mean-square with epsilon."""
+    u = np.asarray(x, dtype=F64) @ np.asarray(noise.W_noise, dtype=F64)
+    s = softplus(u)
+    r = np.sqrt((s * s).mean(axis=1, keepdims=True) + noise.eps)
+    return noise.gamma * s / r, u, s, r
+
+
+def router_logits(x, W_gate, logit_bias=None, noise: Optional["Noise"] = None):
+    """H(x) = x W_g (+ bias) (+ the noise term when asked for)."""
     l = np.asarray(x, dtype=F64) @ np.asarray(W_gate, dtype=F64)
     if logit_bias is not None:
         l = l + np.asarray(logit_bias, dtype=F64)[None, :]
+    if noise is not None:
+        l = l + noise_term(x, noise)[0]
     return l
 
 
@@ -165,13 +205,71 @@ def permutation_from_indices(idx, n_experts):
     return counts, offsets, row_of.reshape(T, k), src_of
 
 
-def route(x, W_gate, n_experts, top_k, logit_bias=None) -> Routing:
-    logits = router_logits(x, W_gate, logit_bias)
+def route(x, W_gate, n_experts, top_k, logit_bias=None, noise=None) -> Routing:
+    logits = router_logits(x, W_gate, logit_bias, noise)
     assert logits.shape[1] == n_experts
     idx = top_k_indices(logits, top_k)
     w = gate_weights(logits, idx)
     counts, offsets, row_of, src_of = permutation_from_indices(idx, n_experts)
     return Routing(idx, w, counts, offsets, row_of, src_of, logits)
+
+
+# --------------------------------------------------------------------------
+# auxiliary load-balance loss  (Sec. 3.2 Eq. 9-12)
+# --------------------------------------------------------------------------
+def router_probs(logits):
+    """p(x): softmax of the router logits over all N experts (Eq. 11)."""
+    l = np.asarray(logits, dtype=F64)
+    e = np.exp(l - l.max(axis=1, keepdims=True))
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def aux_loss(logits, alpha):
+    """L_a = alpha N sum_i f_i P_i (Eq. 9) with f_i the fraction of tokens whose largest probability is
+    expert i (Eq. 10) and P_i the mean probability of expert i (Eq. 12).  Returns (L_a, f, P, p)."""
+    p = router_probs(logits)
+    T, N = p.shape
+    first = np.argmax(np.asarray(logits, dtype=F64), axis=1)   # argmax p = argmax logits; ties -> lower index
+    f = np.bincount(first, minlength=N).astype(F64) / T
+    P = p.mean(axis=0)
+    return float(alpha) * N * float((f * P).sum()), f, P, p
+
+
+def aux_loss_dlogits(logits, alpha):
+    """d L_a / d logits with f held constant: L_a = sum_t <c, p_t>, c_i = alpha N f_i / T, and the softmax
+    Jacobian gives dl_t = p_t * (c - <c, p_t>)."""
+    _, f, _, p = aux_loss(logits, alpha)
+    T, N = p.shape
+    c = float(alpha) * N * f / T
+    return p * (c[None, :] - (p * c[None, :]).sum(axis=1, keepdims=True))
+
+
+# --------------------------------------------------------------------------
+# routing statistics  (Appendix A tables; Sec. 4.3 workload measure)
+# --------------------------------------------------------------------------
+@dataclass
+class RoutingStats:
+    slot_counts: np.ndarray   # [k, N] int64: tokens whose j-th choice is expert i
+    slot_ratio: np.ndarray    # [k] max/min of each row (inf when an expert got none)
+    total_ratio: float        # max/min of the column sums
+    avg_hidden: float         # sum_i n_i h_i / sum_i n_i over all (token, slot) choices
+
+
+def slot_count_stats(slot_counts, d_ff) -> RoutingStats:
+    c = np.asarray(slot_counts, dtype=np.int64)
+    with np.errstate(divide="ignore"):
+        slot_ratio = c.max(axis=1) / c.min(axis=1).astype(F64)
+        tot = c.sum(axis=0)
+        total_ratio = float(tot.max() / F64(tot.min()))
+    avg = float((tot * np.asarray(d_ff, dtype=F64)).sum() / tot.sum()) if tot.sum() else 0.0
+    return RoutingStats(c, slot_ratio, total_ratio, avg)
+
+
+def routing_stats(topk_idx, d_ff) -> RoutingStats:
+    idx = np.asarray(topk_idx)
+    N = len(d_ff)
+    c = np.stack([np.bincount(idx[:, j], minlength=N) for j in range(idx.shape[1])])
+    return slot_count_stats(c, d_ff)
 
 
 # --------------------------------------------------------------------------
@@ -205,7 +303,7 @@ def layer_fwd_dense(x, W_gate, W1, W3, W2, d_ff, top_k, logit_bias=None):
 
 
 def layer_fwd(x, W_gate, W1, W3, W2, d_ff, top_k, logit_bias=None, routing: Optional[Routing] = None,
-              topk_idx=None):
+              topk_idx=None, noise=None):
     """Same sum restricted to its non-zero terms: expert i is evaluated only on
     the tokens that kept it.  `topk_idx` (optional) overrides the selection,
     for staged parity checks; gate weights are then computed from the oracle's
@@ -214,7 +312,7 @@ def layer_fwd(x, W_gate, W1, W3, W2, d_ff, top_k, logit_bias=None, routing: Opti
     T, d = x.shape
     N = len(d_ff)
     if routing is None:
-        logits = router_logits(x, W_gate, logit_bias)
+        logits = router_logits(x, W_gate, logit_bias, noise)
         idx = top_k_indices(logits, top_k) if topk_idx is None else np.asarray(topk_idx)
         w = gate_weights(logits, idx)
     else:
@@ -240,6 +338,8 @@ class Grads:
     dW3: np.ndarray       # [F, d]
     dW2: np.ndarray       # [d*F] flat, packed like W2
     dlogits: np.ndarray   # [T, N]
+    dW_noise: Optional[np.ndarray] = None   # [d, N] when the noise term is on
+    dgamma: Optional[float] = None
 
 
 def gate_backward(w, dg):
@@ -248,8 +348,23 @@ def gate_backward(w, dg):
     return w * (dg - (w * dg).sum(axis=1, keepdims=True))
 
 
+def noise_backward(x, noise: "Noise", dlogits):
+    """Gradients of the noise term z = gamma s / r, s = softplus(u), u = x W_n, r = sqrt(mean_i s_i^2 + eps)
+    given d loss / d z = dlogits.  Returns (dX contribution, dW_noise, dgamma)."""
+    x = np.asarray(x, dtype=F64)
+    Wn = np.asarray(noise.W_noise, dtype=F64)
+    _, u, s, r = noise_term(x, noise)
+    N = s.shape[1]
+    dgamma = float((dlogits * s / r).sum())
+    # z_i = gamma s_i / r(s):  dz_i/ds_j = gamma (delta_ij / r - s_i s_j / (N r^3))
+    ds = noise.gamma * (dlogits / r - s * (dlogits * s).sum(axis=1, keepdims=True) / (N * r ** 3))
+    du = ds / (1.0 + np.exp(-u))           # d softplus(u)/du = sigmoid(u)
+    return du @ Wn.T, x.T @ du, dgamma
+
+
 def layer_bwd(x, W_gate, W1, W3, W2, d_ff, top_k, dY, logit_bias=None, topk_idx=None,
-              need_weight_grads=True) -> Grads:
+              need_weight_grads=True, noise=None, aux_alpha=None, aux_grad=1.0) -> Grads:
+    """Gradients of  loss = <dY, y> + aux_grad * L_a  (the second term only when aux_alpha is given)."""
     x = np.asarray(x, dtype=F64)
     dY = np.asarray(dY, dtype=F64)
     Wg = np.asarray(W_gate, dtype=F64)
@@ -257,7 +372,7 @@ def layer_bwd(x, W_gate, W1, W3, W2, d_ff, top_k, dY, logit_bias=None, topk_idx=
     N = len(d_ff)
     foff = expert_offsets(d_ff)
     F = foff[-1]
-    logits = router_logits(x, Wg, logit_bias)
+    logits = router_logits(x, Wg, logit_bias, noise)
     idx = top_k_indices(logits, top_k) if topk_idx is None else np.asarray(topk_idx)
     w = gate_weights(logits, idx)
 
@@ -290,9 +405,15 @@ def layer_bwd(x, W_gate, W1, W3, W2, d_ff, top_k, dY, logit_bias=None, topk_idx=
     dl = gate_backward(w, dg)
     dlogits = np.zeros((T, N))
     dlogits[np.arange(T)[:, None], idx] = dl
+    if aux_alpha is not None:
+        dlogits += float(aux_grad) * aux_loss_dlogits(logits, aux_alpha)
     dW_gate = x.T @ dlogits
     dX += dlogits @ Wg.T
-    return Grads(dX, dW_gate, dW1, dW3, dW2, dlogits)
+    dW_noise = dgamma = None
+    if noise is not None:
+        dx_n, dW_noise, dgamma = noise_backward(x, noise, dlogits)
+        dX += dx_n
+    return Grads(dX, dW_gate, dW1, dW3, dW2, dlogits, dW_noise, dgamma)
 
 
 def wgrad_columns(x, W_gate, W1, W3, W2, d_ff, top_k, dY, e, cols, logit_bias=None, topk_idx=None):
