@@ -113,6 +113,65 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
                              const void* dY, void* dX, float* dW_gate, float* dW1, float* dW3, float* dW2,
                              int accumulate, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------------- optional parts of the gate
+ * One struct switches on the two parts of the paper's gate that the plain
+ * entry points leave out.  All pointers are DEVICE pointers owned by the
+ * caller; the forward call fills the outputs, the backward call reads them.
+ *
+ * Noise term (second term of H(x) in Sec. 2, with Eq. 4 RMSNorm and Eq. 5
+ * Softplus): H(x)_i += gamma * s_i / sqrt(mean_j s_j^2 + eps), s = Softplus(x
+ * W_noise), the norm taken over the N per-expert values of one token.  It has
+ * no random factor, so it is a function of x.  On when W_noise != NULL; then
+ * gamma and noise_pre are required.
+ *
+ * Auxiliary load-balance loss (Sec. 3.2 Eq. 9-12): p(x) = softmax of H(x) over
+ * all N experts, f_i = share of tokens whose largest probability is expert i
+ * (ties to the lower index), P_i = mean of p_i, L_a = aux_alpha N sum_i f_i
+ * P_i.  On when probs != NULL; then aux_f, aux_P and aux_loss are required. */
+typedef struct {
+  const void* W_noise; /* [d,N], desc.dtype, or NULL */
+  const float* gamma;  /* [1] RMSNorm gain */
+  float eps;           /* RMSNorm epsilon, >= 0 */
+  float* noise_pre;    /* [T,N] x W_noise: written by forward, read by backward */
+  float aux_alpha;     /* alpha of Eq. 9 */
+  float* probs;        /* [T,N] p(x): written by forward, read by backward; or NULL */
+  float* aux_f;        /* [N] f_i: written by forward, read by backward */
+  float* aux_P;        /* [N] P_i */
+  float* aux_loss;     /* [1] L_a */
+} modse_gate_ext;
+
+/* modse_route / modse_layer_fwd with the optional gate parts; ext == NULL is
+ * the plain call.  Same workspace sizes.  An incomplete ext (a switched-on
+ * part with a missing pointer, eps < 0) returns MODSE_ERR_INVALID_ARG. */
+modse_status modse_route_ext(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                             const float* logit_bias, const modse_gate_ext* ext, const modse_routing* out, void* ws,
+                             size_t ws_bytes, void* hip_stream);
+modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                                 const float* logit_bias, const modse_gate_ext* ext, const void* W1, const void* W3,
+                                 const void* W2, void* y, const modse_routing* routing_out, void* saved, void* ws,
+                                 size_t ws_bytes, void* hip_stream);
+
+/* Backward pass of loss = <dY, y> + aux_grad * L_a through the gate with its
+ * optional parts: adds aux_grad * dL_a/dH (f_i held constant, as it is
+ * piecewise constant) to the gradient of the logits, and, when the noise term
+ * is on, also returns dW_noise [d,N] float32 and dgamma [1] float32 (both
+ * follow `accumulate`) and adds the term's share to dX.  ext must hold the
+ * buffers the forward call filled. */
+modse_status modse_layer_bwd_ext(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                                 const modse_gate_ext* ext, float aux_grad, const void* W1, const void* W3,
+                                 const void* W2, const modse_routing* routing, const void* saved, const void* dY,
+                                 void* dX, float* dW_gate, float* dW_noise, float* dgamma, float* dW1, float* dW3,
+                                 float* dW2, int accumulate, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Routing statistics in the shape of the paper's Appendix A tables, from
+ * routing->topk_idx: slot_counts [top_k,N] int32 DEVICE out (tokens whose j-th
+ * choice is expert i); summary [top_k+2] float32 DEVICE out: max/min of each
+ * slot's counts, max/min of the per-expert totals, and the average hidden
+ * width of the chosen experts (the workload measure of Sec. 4.3).  A ratio
+ * whose minimum is 0 reads +inf. */
+modse_status modse_routing_stats(const modse_desc* desc, int64_t T, const modse_routing* routing,
+                                 int32_t* slot_counts, float* summary, void* hip_stream);
+
 /* Per-stage timing for benchmarks.  When enabled, modse_layer_fwd/bwd record
  * HIP events between their stages on the caller's stream; modse_stage_times
  * waits for the last recorded call and returns milliseconds per stage

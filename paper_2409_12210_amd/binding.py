@@ -32,6 +32,12 @@ class _Routing(C.Structure):
                 ("row_of", C.c_void_p), ("src_of", C.c_void_p), ("near_tie_count", C.c_void_p)]
 
 
+class _GateExt(C.Structure):
+    _fields_ = [("W_noise", C.c_void_p), ("gamma", C.c_void_p), ("eps", C.c_float), ("noise_pre", C.c_void_p),
+                ("aux_alpha", C.c_float), ("probs", C.c_void_p), ("aux_f", C.c_void_p), ("aux_P", C.c_void_p),
+                ("aux_loss", C.c_void_p)]
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, "libmodse.so")
 
@@ -54,9 +60,16 @@ def load_library():
     lib.modse_route.argtypes = [dp, i64, vp, vp, vp, rp, vp, sz, vp]
     lib.modse_layer_fwd.argtypes = [dp, i64, vp, vp, vp, vp, vp, vp, vp, rp, vp, vp, sz, vp]
     lib.modse_layer_bwd.argtypes = [dp, i64, vp, vp, vp, vp, vp, rp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+    ep = C.POINTER(_GateExt)
+    lib.modse_route_ext.argtypes = [dp, i64, vp, vp, vp, ep, rp, vp, sz, vp]
+    lib.modse_layer_fwd_ext.argtypes = [dp, i64, vp, vp, vp, ep, vp, vp, vp, vp, rp, vp, vp, sz, vp]
+    lib.modse_layer_bwd_ext.argtypes = [dp, i64, vp, vp, ep, C.c_float, vp, vp, vp, rp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                        vp, C.c_int, vp, sz, vp]
+    lib.modse_routing_stats.argtypes = [dp, i64, rp, vp, vp, vp]
     lib.modse_stage_timing_enable.argtypes = [C.c_int]
     lib.modse_stage_times.argtypes = [C.POINTER(C.c_float)]
     for name in ("modse_workspace_size", "modse_saved_size", "modse_route", "modse_layer_fwd", "modse_layer_bwd",
+                 "modse_route_ext", "modse_layer_fwd_ext", "modse_layer_bwd_ext", "modse_routing_stats",
                  "modse_stage_timing_enable", "modse_stage_times"):
         getattr(lib, name).restype = C.c_int
     _LIB = lib
@@ -132,6 +145,25 @@ class Routing:
                           ("topk_idx", "topk_w", "counts", "offsets", "row_of", "src_of", "near_tie_count")])
 
 
+@dataclass
+class GateExt:
+    """Optional parts of the gate (see modse_gate_ext in include/modse.h): device tensors or None."""
+    W_noise: object = None
+    gamma: object = None
+    eps: float = 0.0
+    noise_pre: object = None
+    aux_alpha: float = 0.0
+    probs: object = None
+    aux_f: object = None
+    aux_P: object = None
+    aux_loss: object = None
+
+    def _c(self):
+        return _GateExt(_ptr(self.W_noise), _ptr(self.gamma), float(self.eps), _ptr(self.noise_pre),
+                        float(self.aux_alpha), _ptr(self.probs), _ptr(self.aux_f), _ptr(self.aux_P),
+                        _ptr(self.aux_loss))
+
+
 def modse_workspace_size(d_model, d_ff, top_k, dtype, T, need_bwd=False, raise_on_error=True):
     out = C.c_size_t(0)
     d = _desc(d_model, d_ff, top_k, dtype)
@@ -179,6 +211,58 @@ def modse_layer_bwd(d_model, d_ff, top_k, dtype, T, x, W_gate, W1, W3, W2, routi
                                           _ptr(dW_gate), _ptr(dW1), _ptr(dW3), _ptr(dW2), int(bool(accumulate)),
                                           _ptr(ws), nbytes, _stream(stream))
     return _check(code, "modse_layer_bwd", raise_on_error)
+
+
+def _nbytes(ws, ws_bytes):
+    return ws_bytes if ws_bytes is not None else (ws.numel() * ws.element_size() if ws is not None else 0)
+
+
+def modse_route_ext(d_model, d_ff, top_k, dtype, T, x, W_gate, logit_bias, ext: Optional[GateExt], routing: Routing,
+                    ws, ws_bytes=None, stream=None, raise_on_error=True) -> int:
+    d = _desc(d_model, d_ff, top_k, dtype)
+    r = routing._c() if routing is not None else None
+    e = ext._c() if ext is not None else None
+    code = load_library().modse_route_ext(C.byref(d), int(T), _ptr(x), _ptr(W_gate), _ptr(logit_bias),
+                                          C.byref(e) if e is not None else None,
+                                          C.byref(r) if r is not None else None, _ptr(ws), _nbytes(ws, ws_bytes),
+                                          _stream(stream))
+    return _check(code, "modse_route_ext", raise_on_error)
+
+
+def modse_layer_fwd_ext(d_model, d_ff, top_k, dtype, T, x, W_gate, logit_bias, ext: Optional[GateExt], W1, W3, W2, y,
+                        routing: Optional[Routing], saved, ws, ws_bytes=None, stream=None, raise_on_error=True) -> int:
+    d = _desc(d_model, d_ff, top_k, dtype)
+    r = routing._c() if routing is not None else None
+    e = ext._c() if ext is not None else None
+    code = load_library().modse_layer_fwd_ext(C.byref(d), int(T), _ptr(x), _ptr(W_gate), _ptr(logit_bias),
+                                              C.byref(e) if e is not None else None, _ptr(W1), _ptr(W3), _ptr(W2),
+                                              _ptr(y), C.byref(r) if r is not None else None, _ptr(saved), _ptr(ws),
+                                              _nbytes(ws, ws_bytes), _stream(stream))
+    return _check(code, "modse_layer_fwd_ext", raise_on_error)
+
+
+def modse_layer_bwd_ext(d_model, d_ff, top_k, dtype, T, x, W_gate, ext: Optional[GateExt], aux_grad, W1, W3, W2,
+                        routing: Routing, saved, dY, dX, dW_gate, dW_noise, dgamma, dW1, dW3, dW2, accumulate, ws,
+                        ws_bytes=None, stream=None, raise_on_error=True) -> int:
+    d = _desc(d_model, d_ff, top_k, dtype)
+    r = routing._c() if routing is not None else None
+    e = ext._c() if ext is not None else None
+    code = load_library().modse_layer_bwd_ext(C.byref(d), int(T), _ptr(x), _ptr(W_gate),
+                                              C.byref(e) if e is not None else None, float(aux_grad), _ptr(W1),
+                                              _ptr(W3), _ptr(W2), C.byref(r) if r is not None else None, _ptr(saved),
+                                              _ptr(dY), _ptr(dX), _ptr(dW_gate), _ptr(dW_noise), _ptr(dgamma),
+                                              _ptr(dW1), _ptr(dW3), _ptr(dW2), int(bool(accumulate)), _ptr(ws),
+                                              _nbytes(ws, ws_bytes), _stream(stream))
+    return _check(code, "modse_layer_bwd_ext", raise_on_error)
+
+
+def modse_routing_stats(d_model, d_ff, top_k, dtype, T, routing: Routing, slot_counts, summary, stream=None,
+                        raise_on_error=True) -> int:
+    d = _desc(d_model, d_ff, top_k, dtype)
+    r = routing._c() if routing is not None else None
+    code = load_library().modse_routing_stats(C.byref(d), int(T), C.byref(r) if r is not None else None,
+                                              _ptr(slot_counts), _ptr(summary), _stream(stream))
+    return _check(code, "modse_routing_stats", raise_on_error)
 
 
 def modse_stage_timing_enable(on: bool) -> int:

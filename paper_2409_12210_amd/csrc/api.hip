@@ -110,7 +110,7 @@ SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
 }
 
 struct BwdLayout {
-  size_t plan[3], Xp, dO, dA, dB, dXp, dg, dWg_partial, total;
+  size_t plan[3], Xp, dO, dA, dB, dXp, dg, dl, du, dgamma_part, dWg_partial, total;
 };
 
 BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
@@ -126,6 +126,9 @@ BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
   w.dB = c.take(h);
   w.dXp = c.take(Tk * L.d * es);
   w.dg = c.take(Tk * 4);
+  w.dl = c.take((size_t)L.T * L.N * 4);
+  w.du = c.take((size_t)L.T * L.N * 4);
+  w.dgamma_part = c.take((((size_t)L.T + 255) / 256) * 4);
   w.dWg_partial = c.take(nb * L.d * L.N * 4);
   w.total = c.off;
   return w;
@@ -193,6 +196,18 @@ bool routing_complete(const modse_routing* r) {
   return r && r->topk_idx && r->topk_w && r->counts && r->offsets && r->row_of && r->src_of && r->near_tie_count;
 }
 
+// A gate extension is usable when every pointer its switched-on parts need is there.
+bool ext_complete(const modse_gate_ext* e) {
+  if (!e) return true;
+  if (e->W_noise && (!e->gamma || !e->noise_pre || !(e->eps >= 0.f))) return false;
+  if (e->probs && (!e->aux_f || !e->aux_P || !e->aux_loss)) return false;
+  return true;
+}
+
+GateExtPtrs ext_ptrs(const modse_gate_ext* e) {
+  return GateExtPtrs{e->W_noise, e->gamma, e->eps, e->noise_pre, e->aux_alpha, e->probs, e->aux_f, e->aux_P, e->aux_loss};
+}
+
 }  // namespace
 
 extern "C" {
@@ -228,10 +243,18 @@ modse_status modse_saved_size(const modse_desc* desc, int64_t T, size_t* bytes) 
 modse_status modse_route(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
                          const float* logit_bias, const modse_routing* out, void* ws, size_t ws_bytes,
                          void* hip_stream) {
+  return modse_route_ext(desc, T, x, W_gate, logit_bias, nullptr, out, ws, ws_bytes, hip_stream);
+}
+
+modse_status modse_route_ext(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                             const float* logit_bias, const modse_gate_ext* ext, const modse_routing* out, void* ws,
+                             size_t ws_bytes, void* hip_stream) {
   const modse_status st = check_desc(desc, T);
   if (st != MODSE_OK) return st;
   if (T == 0) return MODSE_OK;
-  if (!x || !W_gate || !ws || !routing_complete(out)) return MODSE_ERR_INVALID_ARG;
+  if (!x || !W_gate || !ws || !routing_complete(out) || !ext_complete(ext)) return MODSE_ERR_INVALID_ARG;
+  GateExtPtrs G;
+  if (ext) G = ext_ptrs(ext);
   const LayerDims L = make_dims(desc, T);
   const FwdLayout w = fwd_layout(L, desc->dtype);
   if (ws_bytes < w.total) return MODSE_ERR_WORKSPACE;
@@ -239,7 +262,17 @@ modse_status modse_route(const modse_desc* desc, int64_t T, const void* x, const
   char* wsb = static_cast<char*>(ws);
   const RoutingPtrs R = routing_from(out, wsb, w);
   HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
-                       nullptr, s));
+                       nullptr, ext ? &G : nullptr, s));
+  return MODSE_OK;
+}
+
+modse_status modse_routing_stats(const modse_desc* desc, int64_t T, const modse_routing* routing,
+                                 int32_t* slot_counts, float* summary, void* hip_stream) {
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  if (!routing || !routing->topk_idx || !slot_counts || !summary) return MODSE_ERR_INVALID_ARG;
+  const LayerDims L = make_dims(desc, T);
+  HIP_TRY(launch_routing_stats(L, routing->topk_idx, slot_counts, summary, static_cast<hipStream_t>(hip_stream)));
   return MODSE_OK;
 }
 
@@ -247,10 +280,20 @@ modse_status modse_layer_fwd(const modse_desc* desc, int64_t T, const void* x, c
                              const float* logit_bias, const void* W1, const void* W3, const void* W2, void* y,
                              const modse_routing* routing_out, void* saved, void* ws, size_t ws_bytes,
                              void* hip_stream) {
+  return modse_layer_fwd_ext(desc, T, x, W_gate, logit_bias, nullptr, W1, W3, W2, y, routing_out, saved, ws, ws_bytes,
+                             hip_stream);
+}
+
+modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                                 const float* logit_bias, const modse_gate_ext* ext, const void* W1, const void* W3,
+                                 const void* W2, void* y, const modse_routing* routing_out, void* saved, void* ws,
+                                 size_t ws_bytes, void* hip_stream) {
   const modse_status st = check_desc(desc, T);
   if (st != MODSE_OK) return st;
   if (T == 0) return MODSE_OK;
-  if (!x || !W_gate || !W1 || !W3 || !W2 || !y || !ws) return MODSE_ERR_INVALID_ARG;
+  if (!x || !W_gate || !W1 || !W3 || !W2 || !y || !ws || !ext_complete(ext)) return MODSE_ERR_INVALID_ARG;
+  GateExtPtrs G;
+  if (ext) G = ext_ptrs(ext);
   if (routing_out && !routing_complete(routing_out)) return MODSE_ERR_INVALID_ARG;
   const modse_dtype dt = desc->dtype;
   const LayerDims L = make_dims(desc, T);
@@ -262,7 +305,8 @@ modse_status modse_layer_fwd(const modse_desc* desc, int64_t T, const void* x, c
   Stamp stamp(0, s);
 
   void* Xp = wsb + w.Xp;
-  HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist), Xp, s));
+  HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist), Xp,
+                       ext ? &G : nullptr, s));
   stamp.mark(MODSE_STAGE_ROUTE);  // routing and the row scatter share kernels; the scatter is counted here
 
   FwdPlanArgs pa;
@@ -295,11 +339,23 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
                              const void* W3, const void* W2, const modse_routing* routing, const void* saved,
                              const void* dY, void* dX, float* dW_gate, float* dW1, float* dW3, float* dW2,
                              int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+  return modse_layer_bwd_ext(desc, T, x, W_gate, nullptr, 0.f, W1, W3, W2, routing, saved, dY, dX, dW_gate, nullptr,
+                             nullptr, dW1, dW3, dW2, accumulate, ws, ws_bytes, hip_stream);
+}
+
+modse_status modse_layer_bwd_ext(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                                 const modse_gate_ext* ext, float aux_grad, const void* W1, const void* W3,
+                                 const void* W2, const modse_routing* routing, const void* saved, const void* dY,
+                                 void* dX, float* dW_gate, float* dW_noise, float* dgamma, float* dW1, float* dW3,
+                                 float* dW2, int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
   const modse_status st = check_desc(desc, T);
   if (st != MODSE_OK) return st;
   if (T == 0) return MODSE_OK;
   if (!x || !W_gate || !W1 || !W3 || !W2 || !saved || !dY || !dX || !dW_gate || !dW1 || !dW3 || !dW2 || !ws)
     return MODSE_ERR_INVALID_ARG;
+  if (!ext_complete(ext) || (ext && ext->W_noise && (!dW_noise || !dgamma))) return MODSE_ERR_INVALID_ARG;
+  GateExtPtrs G;
+  if (ext) G = ext_ptrs(ext);
   if (!routing_complete(routing)) return MODSE_ERR_INVALID_ARG;
   const modse_dtype dt = desc->dtype;
   const LayerDims L = make_dims(desc, T);
@@ -343,8 +399,11 @@ modse_status modse_layer_bwd(const modse_desc* desc, int64_t T, const void* x, c
   HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.wg, accumulate, 0, 2 * wg13 + wg2, s));
   stamp.mark(MODSE_STAGE_BWD_WGRAD);
 
-  HIP_TRY(launch_bwd_router(L, dt, x, W_gate, pa.dXp, dg, R, dX, reinterpret_cast<float*>(wsb + w.dWg_partial),
-                            dW_gate, accumulate, s));
+  const BwdRouterBufs rb = {reinterpret_cast<float*>(wsb + w.dl), reinterpret_cast<float*>(wsb + w.du),
+                            reinterpret_cast<float*>(wsb + w.dgamma_part),
+                            reinterpret_cast<float*>(wsb + w.dWg_partial)};
+  HIP_TRY(launch_bwd_router(L, dt, x, W_gate, pa.dXp, dg, R, ext ? &G : nullptr, aux_grad, rb, dX, dW_gate, dW_noise,
+                            dgamma, accumulate, s));
   stamp.mark(MODSE_STAGE_BWD_ROUTER);
   return MODSE_OK;
 }

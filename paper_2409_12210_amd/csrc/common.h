@@ -120,18 +120,40 @@ struct RoutingPtrs {
   int32_t* near_tie_count;
 };
 
+// Optional parts of the gate (device pointers; null W_noise = no noise term, null probs = no auxiliary loss).
+struct GateExtPtrs {
+  const void* W_noise;  // [d, N], layer dtype
+  const float* gamma;   // [1]
+  float eps;
+  float* noise_pre;     // [T, N]  x W_noise
+  float alpha;
+  float* probs;         // [T, N]  softmax of H(x) over all experts
+  float* aux_f;         // [N]
+  float* aux_P;         // [N]
+  float* aux_loss;      // [1]
+};
+
 // ---------------------------------------------------------------- launchers
 // route.hip
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
-                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, hipStream_t s);
+                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, const GateExtPtrs* G, hipStream_t s);
+hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,
+                                hipStream_t s);
 hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, const RoutingPtrs& R, void* y,
                           hipStream_t s);
 hipError_t launch_bwd_prep(const LayerDims& L, modse_dtype dt, const void* dY, const void* O, const RoutingPtrs& R,
                            void* dO, float* dg, hipStream_t s);
 hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, void* Xp,
                               hipStream_t s);
+struct BwdRouterBufs {  // workspace of the router's backward pass
+  float* dl;           // [T, N] dense gradient of the logits
+  float* du;           // [T, N] gradient of x W_noise
+  float* dgamma_part;  // [ceil(T / 256)]
+  float* dW_partial;   // [ceil(T / 64), d, N] per-block shares of a router-side weight gradient
+};
 hipError_t launch_bwd_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const void* dXp,
-                             const float* dg, const RoutingPtrs& R, void* dX, float* dWg_partial, float* dW_gate,
+                             const float* dg, const RoutingPtrs& R, const GateExtPtrs* G, float aux_grad,
+                             const BwdRouterBufs& B, void* dX, float* dW_gate, float* dW_noise, float* dgamma,
                              int accumulate, hipStream_t s);
 
 // gemm.hip

@@ -4,6 +4,8 @@
 // arXiv 2409.12210).  Logits are accumulated in float64: products of bf16 or fp32 inputs are exact in
 // float64, so the integer routing decision is taken at the same precision as a float64 reference and
 // does not depend on summation order beyond the last bit.
+#include <climits>
+
 #include "common.h"
 
 namespace {
@@ -71,17 +73,26 @@ __device__ inline void load_row(const T* p, float* out) {
   }
 }
 
+__device__ inline double softplus_f64(double u) {  // log(1 + exp(u)) without overflow
+  return u > 0.0 ? u + log1p(exp(-u)) : log1p(exp(u));
+}
+
 // One block routes TPB consecutive tokens.  blockhist[b][0..N-1] = this block's per-expert assignment
 // counts, blockhist[b][N] = its near-tie token count.
-template <typename T, int NE, int TOK>
+// EXT adds the optional parts of the gate: the noise term RMSNorm(Softplus(x W_n)) of H(x) (Sec. 2 Eq. 4-5;
+// G.Wn != null) and the full-softmax probabilities p(x) that the auxiliary loss needs (Sec. 3.2 Eq. 11;
+// G.probs != null).  Both reuse the x rows this kernel already holds in registers.
+template <typename T, int NE, int TOK, bool EXT>
 __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
                                                                const float* __restrict__ bias, int ntok, int d, int N,
                                                                int top_k, int32_t* __restrict__ topk_idx,
                                                                float* __restrict__ topk_w,
-                                                               int32_t* __restrict__ blockhist) {
+                                                               int32_t* __restrict__ blockhist, GateExtPtrs G) {
   constexpr int V = NE * TOK;
   __shared__ double s_logit[ROUTE_THREADS / 64][TOK][NE];
+  __shared__ double s_u[EXT ? ROUTE_THREADS / 64 : 1][EXT ? TOK : 1][EXT ? NE : 1];
   __shared__ int s_hist[MODSE_MAX_EXPERTS + 1];
+  const T* Wn = EXT ? static_cast<const T*>(G.W_noise) : nullptr;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tok0 = blockIdx.x * TPB + wave * TOK_PER_WAVE;
   if (tid <= N) s_hist[tid] = 0;
@@ -89,9 +100,13 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
 
   for (int pass = 0; pass < TOK_PER_WAVE / TOK; ++pass) {
     const int tbase = tok0 + pass * TOK;
-    double acc[V];
+    double acc[V], acc2[EXT ? V : 1];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.0;
+    if (EXT) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc2[EXT ? i : 0] = 0.0;
+    }
     for (int c = lane * 8; c < d; c += 64 * 8) {
       float xv[TOK][8];
 #pragma unroll
@@ -101,7 +116,9 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {  // one W_gate row at a time keeps the register footprint small
-        double w[NE];
+        double xd[TOK];
+#pragma unroll
+        for (int tt = 0; tt < TOK; ++tt) xd[tt] = (double)xv[tt][i];
         const T* wrow = Wg + (size_t)(c + i) * N;
         float wf[NE];
         if (N == NE) {
@@ -111,12 +128,25 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
           for (int e = 0; e < NE; ++e) wf[e] = (float)wrow[min(e, N - 1)];
         }
 #pragma unroll
-        for (int e = 0; e < NE; ++e) w[e] = (double)wf[e];
+        for (int e = 0; e < NE; ++e) {
+          const double wd = (double)wf[e];
 #pragma unroll
-        for (int tt = 0; tt < TOK; ++tt) {
-          const double xd = (double)xv[tt][i];
+          for (int tt = 0; tt < TOK; ++tt) acc[tt * NE + e] = fma(xd[tt], wd, acc[tt * NE + e]);
+        }
+        if (EXT && Wn) {  // the same x values against the noise matrix
+          const T* nrow = Wn + (size_t)(c + i) * N;
+          if (N == NE) {
+            load_row<NE>(nrow, wf);
+          } else {
 #pragma unroll
-          for (int e = 0; e < NE; ++e) acc[tt * NE + e] = fma(xd, w[e], acc[tt * NE + e]);
+            for (int e = 0; e < NE; ++e) wf[e] = (float)nrow[min(e, N - 1)];
+          }
+#pragma unroll
+          for (int e = 0; e < NE; ++e) {
+            const double wd = (double)wf[e];
+#pragma unroll
+            for (int tt = 0; tt < TOK; ++tt) acc2[EXT ? tt * NE + e : 0] = fma(xd[tt], wd, acc2[EXT ? tt * NE + e : 0]);
+          }
         }
       }
     }
@@ -125,14 +155,38 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
       const int v = bitrev<Log2<V>::value>(lane);
       s_logit[wave][v / NE][v % NE] = acc[0];
     }
+    if constexpr (EXT) {
+      if (Wn) {
+        wave_sum_values<V>(acc2, lane);
+        if (lane < V) {
+          const int v = bitrev<Log2<V>::value>(lane);
+          s_u[wave][v / NE][v % NE] = acc2[0];
+        }
+      }
+    }
     __syncthreads();
     if (lane < TOK && tbase + lane < ntok) {
       const int t = tbase + lane;
+      if (bias)
+        for (int e = 0; e < N; ++e) s_logit[wave][lane][e] += (double)bias[e];
+      if constexpr (EXT) {
+        if (Wn) {  // H(x)_e += gamma s_e / sqrt(mean_i s_i^2 + eps),  s = softplus(x W_n)
+          double ss = 0.0;
+          for (int e = 0; e < N; ++e) {
+            const double u = s_u[wave][lane][e];
+            G.noise_pre[(size_t)t * N + e] = (float)u;
+            const double sp = softplus_f64(u);
+            s_u[wave][lane][e] = sp;
+            ss += sp * sp;
+          }
+          const double scale = (double)G.gamma[0] / sqrt(ss / N + (double)G.eps);
+          for (int e = 0; e < N; ++e) s_logit[wave][lane][e] += scale * s_u[wave][lane][e];
+        }
+      }
       double m1 = -INFINITY, m2 = -INFINITY, m3 = -INFINITY;
       int i1 = 0, i2 = 0;
       for (int e = 0; e < N; ++e) {
-        double l = s_logit[wave][lane][e];
-        if (bias) l += (double)bias[e];
+        const double l = s_logit[wave][lane][e];
         if (l > m1) {  // strict comparisons while scanning upward: ties stay with the lower index
           m3 = m2; m2 = m1; i2 = i1; m1 = l; i1 = e;
         } else if (l > m2) {
@@ -158,6 +212,13 @@ __global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restri
         near = (N > 1 && m1 - m2 < 1e-6);
       }
       if (near) atomicAdd(&s_hist[N], 1);
+      if constexpr (EXT) {
+        if (G.probs) {  // p(x) = softmax over all N logits
+          double den = 0.0;
+          for (int e = 0; e < N; ++e) den += exp(s_logit[wave][lane][e] - m1);
+          for (int e = 0; e < N; ++e) G.probs[(size_t)t * N + e] = (float)(exp(s_logit[wave][lane][e] - m1) / den);
+        }
+      }
     }
     __syncthreads();
   }
@@ -222,6 +283,87 @@ __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ b
     }
     offsets[N] = run;
     near_tie_count[0] = s_total[N];
+  }
+}
+
+// Auxiliary load-balance loss (Sec. 3.2 Eq. 9-12), single block: f_i = share of tokens whose first choice is
+// expert i, P_i = mean of p_i, L_a = alpha N sum_i f_i P_i.  Every thread sums its tokens in ascending
+// order and the per-thread sums are added in thread order, so the result does not depend on timing.
+__global__ __launch_bounds__(256) void aux_finish_kernel(const float* __restrict__ probs,
+                                                         const int32_t* __restrict__ topk_idx, int ntok, int N,
+                                                         int top_k, float alpha, float* __restrict__ f_out,
+                                                         float* __restrict__ P_out, float* __restrict__ loss) {
+  __shared__ float s_p[256];
+  __shared__ int s_c[256];
+  __shared__ float s_f[MODSE_MAX_EXPERTS], s_P[MODSE_MAX_EXPERTS];
+  const int tid = threadIdx.x;
+  for (int e = 0; e < N; ++e) {
+    float acc = 0.f;
+    int cnt = 0;
+    for (int t = tid; t < ntok; t += 256) {
+      acc += probs[(size_t)t * N + e];
+      cnt += topk_idx[(size_t)t * top_k] == e ? 1 : 0;
+    }
+    s_p[tid] = acc;
+    s_c[tid] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.f;
+      int c = 0;
+      for (int i = 0; i < 256; ++i) {
+        tot += s_p[i];
+        c += s_c[i];
+      }
+      s_P[e] = tot / (float)ntok;
+      s_f[e] = (float)c / (float)ntok;
+    }
+    __syncthreads();
+  }
+  if (tid < N) {
+    f_out[tid] = s_f[tid];
+    P_out[tid] = s_P[tid];
+  }
+  if (tid == 0) {
+    float l = 0.f;
+    for (int e = 0; e < N; ++e) l += s_f[e] * s_P[e];
+    loss[0] = alpha * (float)N * l;
+  }
+}
+
+// Routing statistics in the shape of the paper's Appendix A tables, single block: slot_counts[j][i] = tokens
+// whose j-th choice is expert i; summary[j] = max/min of row j, summary[k] = max/min of the per-expert
+// totals, summary[k+1] = average hidden width of the chosen experts (Sec. 4.3).
+__global__ __launch_bounds__(256) void routing_stats_kernel(const int32_t* __restrict__ topk_idx, int ntok, int N,
+                                                            int top_k, LayerDims L, int32_t* __restrict__ slot_counts,
+                                                            float* __restrict__ summary) {
+  __shared__ int s_cnt[2][MODSE_MAX_EXPERTS];
+  const int tid = threadIdx.x;
+  if (tid < 2 * MODSE_MAX_EXPERTS) (&s_cnt[0][0])[tid] = 0;
+  __syncthreads();
+  for (int i = tid; i < ntok * top_k; i += 256) atomicAdd(&s_cnt[i % top_k][topk_idx[i]], 1);
+  __syncthreads();
+  for (int i = tid; i < top_k * N; i += 256) slot_counts[i] = s_cnt[i / N][i % N];
+  if (tid == 0) {
+    double wsum = 0.0;
+    long tot_all = 0;
+    int tmax = 0, tmin = INT_MAX;
+    for (int e = 0; e < N; ++e) {
+      const int tot = s_cnt[0][e] + (top_k == 2 ? s_cnt[1][e] : 0);
+      tmax = max(tmax, tot);
+      tmin = min(tmin, tot);
+      wsum += (double)tot * L.f[e];
+      tot_all += tot;
+    }
+    for (int j = 0; j < top_k; ++j) {
+      int mx = 0, mn = INT_MAX;
+      for (int e = 0; e < N; ++e) {
+        mx = max(mx, s_cnt[j][e]);
+        mn = min(mn, s_cnt[j][e]);
+      }
+      summary[j] = mn > 0 ? (float)mx / (float)mn : INFINITY;
+    }
+    summary[top_k] = tmin > 0 ? (float)tmax / (float)tmin : INFINITY;
+    summary[top_k + 1] = tot_all > 0 ? (float)(wsum / (double)tot_all) : 0.f;
   }
 }
 
@@ -354,118 +496,102 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const T* __restrict__ dY,
   if (lane == 0) dg[r] = dot;
 }
 
-// Backward through the gate and the router for TPB tokens per block:
-//   dl_j = g_j (dg_j - sum_m g_m dg_m) on the kept logits, 0 elsewhere  (softmax over KeepTopK)
-//   dX[t] = sum_j dXp[row_of[t,j]] + W_gate dl
-//   partial[b] = sum_{t in block} x[t] (outer) dl[t]     (reduced over blocks by dwg_reduce_kernel)
-template <typename T>
-__global__ __launch_bounds__(ROUTE_THREADS) void bwd_router_kernel(
-    const T* __restrict__ x, const T* __restrict__ Wg, const T* __restrict__ dXp, const float* __restrict__ dg,
-    int ntok, int d, int N, int top_k, const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
-    const int32_t* __restrict__ row_of, T* __restrict__ dX, float* __restrict__ partial) {
-  __shared__ float s_dl[TPB][MODSE_MAX_EXPERTS];
-  __shared__ int s_row[TPB][2];
-  __shared__ int s_idx[TPB][2];
-  __shared__ float s_dlk[TPB][2];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int t0 = blockIdx.x * TPB;
-  for (int i = tid; i < TPB * MODSE_MAX_EXPERTS; i += ROUTE_THREADS) (&s_dl[0][0])[i] = 0.f;
-  __syncthreads();
-  if (tid < TPB && t0 + tid < ntok) {
-    const int t = t0 + tid;
+// Backward through the gate, one thread per token: the dense gradient of the logits H(x),
+//   dl_j = g_j (dg_j - sum_m g_m dg_m) on the kept logits (softmax over KeepTopK), 0 elsewhere,
+//   + aux_coef p_i (f_i - sum_m f_m p_m)  when the auxiliary loss is on (Sec. 3.2 Eq. 9-12 with f constant;
+//     aux_coef = dLoss/dL_a * alpha N / T),
+// and, when the noise term is on (z = gamma s / r, s = softplus(u), r = sqrt(mean s^2 + eps), Sec. 2
+// Eq. 4-5), the gradient of u = x W_n and this block's share of d gamma:
+//   du_i = gamma (dl_i / r - s_i <s, dl> / (N r^3)) sigmoid(u_i),   dgamma = sum_t <dl, s> / r.
+__global__ __launch_bounds__(256) void gate_bwd_kernel(const float* __restrict__ dg, int ntok, int N, int top_k,
+                                                       const int32_t* __restrict__ topk_idx,
+                                                       const float* __restrict__ topk_w,
+                                                       const int32_t* __restrict__ row_of, GateExtPtrs G,
+                                                       float aux_coef, float* __restrict__ dl, float* __restrict__ du,
+                                                       float* __restrict__ dgamma_part) {
+  __shared__ float s_red[256];
+  const int tid = threadIdx.x;
+  const int t = blockIdx.x * 256 + tid;
+  float dgam = 0.f;
+  if (t < ntok) {
+    float* row = dl + (size_t)t * N;
+    if (G.probs && aux_coef != 0.f) {
+      const float* p = G.probs + (size_t)t * N;
+      float fp = 0.f;
+      for (int e = 0; e < N; ++e) fp = fmaf(G.aux_f[e], p[e], fp);
+      for (int e = 0; e < N; ++e) row[e] = aux_coef * p[e] * (G.aux_f[e] - fp);
+    } else {
+      for (int e = 0; e < N; ++e) row[e] = 0.f;
+    }
     float g[2] = {0.f, 0.f}, dgv[2] = {0.f, 0.f};
     float mean = 0.f;
     for (int j = 0; j < top_k; ++j) {
-      const int r = row_of[(size_t)t * top_k + j];
-      s_row[tid][j] = r;
-      s_idx[tid][j] = topk_idx[(size_t)t * top_k + j];
       g[j] = topk_w[(size_t)t * top_k + j];
-      dgv[j] = dg[r];
+      dgv[j] = dg[row_of[(size_t)t * top_k + j]];
       mean += g[j] * dgv[j];
     }
-    for (int j = 0; j < top_k; ++j) {
-      const float dl = g[j] * (dgv[j] - mean);
-      s_dlk[tid][j] = dl;
-      s_dl[tid][s_idx[tid][j]] = dl;
-    }
-  }
-  __syncthreads();
-  for (int i = 0; i < TOK_PER_WAVE; ++i) {
-    const int tl = wave * TOK_PER_WAVE + i;
-    const int t = t0 + tl;
-    if (t >= ntok) break;
-    const int r0 = s_row[tl][0], e0 = s_idx[tl][0];
-    const float dl0 = s_dlk[tl][0];
-    const int r1 = top_k == 2 ? s_row[tl][1] : 0, e1 = top_k == 2 ? s_idx[tl][1] : 0;
-    const float dl1 = top_k == 2 ? s_dlk[tl][1] : 0.f;
-    for (int c = lane * 8; c < d; c += 64 * 8) {
-      float a[8], o[8];
-      load8(dXp + (size_t)r0 * d + c, a);
-#pragma unroll
-      for (int q = 0; q < 8; ++q) o[q] = a[q] + dl0 * (float)Wg[(size_t)(c + q) * N + e0];
-      if (top_k == 2) {
-        load8(dXp + (size_t)r1 * d + c, a);
-#pragma unroll
-        for (int q = 0; q < 8; ++q) o[q] += a[q] + dl1 * (float)Wg[(size_t)(c + q) * N + e1];
+    for (int j = 0; j < top_k; ++j) row[topk_idx[(size_t)t * top_k + j]] += g[j] * (dgv[j] - mean);
+    if (G.W_noise) {
+      const float* u = G.noise_pre + (size_t)t * N;
+      float ss = 0.f, sd = 0.f;
+      for (int e = 0; e < N; ++e) {
+        const float sp = u[e] > 15.f ? u[e] : log1pf(__expf(u[e]));
+        ss = fmaf(sp, sp, ss);
+        sd = fmaf(sp, row[e], sd);
       }
-      store8(dX + (size_t)t * d + c, o);
+      const float r = sqrtf(ss / (float)N + G.eps), gam = G.gamma[0];
+      const float k1 = gam / r, k2 = gam * sd / ((float)N * r * r * r);
+      for (int e = 0; e < N; ++e) {
+        const float sp = u[e] > 15.f ? u[e] : log1pf(__expf(u[e]));
+        du[(size_t)t * N + e] = (k1 * row[e] - k2 * sp) / (1.f + __expf(-u[e]));
+      }
+      dgam = sd / r;
     }
   }
-  const int nt = min(TPB, ntok - t0);
-  for (int c = tid; c < d; c += ROUTE_THREADS) {
-    float xcol[TPB];
-#pragma unroll
-    for (int tl = 0; tl < TPB; ++tl) xcol[tl] = tl < nt ? (float)x[(size_t)(t0 + tl) * d + c] : 0.f;
-    for (int e = 0; e < N; ++e) {
-      float acc = 0.f;
-#pragma unroll
-      for (int tl = 0; tl < TPB; ++tl) acc = fmaf(xcol[tl], s_dl[tl][e], acc);
-      partial[((size_t)blockIdx.x * d + c) * N + e] = acc;
+  if (dgamma_part) {  // fixed-order sum over the block
+    s_red[tid] = dgam;
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.f;
+      for (int i = 0; i < 256; ++i) tot += s_red[i];
+      dgamma_part[blockIdx.x] = tot;
     }
   }
 }
 
-// Same as bwd_router_kernel for N <= 8, one pass over the data: a thread owns 8 columns of d for all
-// BR_TOK tokens of the block, keeps the 8 x 8 slice of W_gate and of the dW_gate partial in registers, and
-// per token reads x and the two dXp rows once (16-byte loads, a full row per block instruction).
+// Backward through a router-side matrix W [d, ldw] (W_gate with dl, or W_noise with du) for BR_TOK tokens per
+// block and up to 8 of its columns [e0, e0 + ne):
+//   dX[t]      = (first ? sum_j dXp[row_of[t, j]] : dX[t]) + W[:, e0 : e0+ne] dl[t, e0 : e0+ne]
+//   partial[b] = sum_{t in block} x[t] (outer) dl[t, e0 : e0+ne]      (reduced over blocks by dwg_reduce_kernel)
+// A thread owns 8 columns of d for all tokens of the block, keeps the 8 x 8 slice of W and of the partial in
+// registers, and per token reads x and the dXp rows once (16-byte loads, a full row per block instruction).
 constexpr int BR_TOK = 64;
 template <typename T>
-__global__ __launch_bounds__(ROUTE_THREADS) void bwd_router8_kernel(
-    const T* __restrict__ x, const T* __restrict__ Wg, const T* __restrict__ dXp, const float* __restrict__ dg,
-    int ntok, int d, int N, int top_k, const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
-    const int32_t* __restrict__ row_of, T* __restrict__ dX, float* __restrict__ partial) {
+__global__ __launch_bounds__(ROUTE_THREADS) void bwd_gate_rows_kernel(
+    const T* __restrict__ x, const T* __restrict__ W, int ldw, int e0, int ne, const T* __restrict__ dXp,
+    const float* __restrict__ dl, int ntok, int d, int top_k, const int32_t* __restrict__ row_of, int first,
+    T* __restrict__ dX, float* __restrict__ partial) {
   __shared__ __attribute__((aligned(16))) float s_dl[BR_TOK][8];
   __shared__ int s_row[BR_TOK][2];
   const int tid = threadIdx.x;
   const int t0 = blockIdx.x * BR_TOK;
-  for (int i = tid; i < BR_TOK * 8; i += ROUTE_THREADS) (&s_dl[0][0])[i] = 0.f;
-  __syncthreads();
-  if (tid < BR_TOK && t0 + tid < ntok) {
-    const int t = t0 + tid;
-    float g[2] = {0.f, 0.f}, dgv[2] = {0.f, 0.f};
-    int idx[2] = {0, 0};
-    float mean = 0.f;
-    for (int j = 0; j < top_k; ++j) {
-      const int r = row_of[(size_t)t * top_k + j];
-      s_row[tid][j] = r;
-      idx[j] = topk_idx[(size_t)t * top_k + j];
-      g[j] = topk_w[(size_t)t * top_k + j];
-      dgv[j] = dg[r];
-      mean += g[j] * dgv[j];
-    }
-    for (int j = 0; j < top_k; ++j) s_dl[tid][idx[j]] = g[j] * (dgv[j] - mean);
+  for (int i = tid; i < BR_TOK * 8; i += ROUTE_THREADS) {
+    const int tl = i >> 3, e = i & 7;
+    (&s_dl[0][0])[i] = (t0 + tl < ntok && e < ne) ? dl[(size_t)(t0 + tl) * ldw + e0 + e] : 0.f;
   }
+  if (first && tid < BR_TOK && t0 + tid < ntok)
+    for (int j = 0; j < top_k; ++j) s_row[tid][j] = row_of[(size_t)(t0 + tid) * top_k + j];
   __syncthreads();
   const int nt = min(BR_TOK, ntok - t0);
   for (int c = tid * 8; c < d; c += ROUTE_THREADS * 8) {
     float wg[8][8], acc[8][8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      if (N == 8) {
-        load8(Wg + (size_t)(c + q) * 8, wg[q]);
+      if (ldw == 8) {
+        load8(W + (size_t)(c + q) * 8, wg[q]);
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) wg[q][e] = e < N ? (float)Wg[(size_t)(c + q) * N + e] : 0.f;
+        for (int e = 0; e < 8; ++e) wg[q][e] = e < ne ? (float)W[(size_t)(c + q) * ldw + e0 + e] : 0.f;
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
@@ -475,12 +601,16 @@ __global__ __launch_bounds__(ROUTE_THREADS) void bwd_router8_kernel(
       float dlv[8], xv[8], a[8], o[8];
       load8(&s_dl[tl][0], dlv);
       load8(x + (size_t)t * d + c, xv);
-      load8(dXp + (size_t)s_row[tl][0] * d + c, a);
-      if (top_k == 2) {
-        float b[8];
-        load8(dXp + (size_t)s_row[tl][1] * d + c, b);
+      if (first) {
+        load8(dXp + (size_t)s_row[tl][0] * d + c, a);
+        if (top_k == 2) {
+          float b[8];
+          load8(dXp + (size_t)s_row[tl][1] * d + c, b);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) a[q] += b[q];
+          for (int q = 0; q < 8; ++q) a[q] += b[q];
+        }
+      } else {
+        load8(dX + (size_t)t * d + c, a);
       }
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
@@ -494,12 +624,12 @@ __global__ __launch_bounds__(ROUTE_THREADS) void bwd_router8_kernel(
       }
       store8(dX + (size_t)t * d + c, o);
     }
-    float* out = partial + ((size_t)blockIdx.x * d + c) * N;
+    float* out = partial + ((size_t)blockIdx.x * d + c) * ldw + e0;
 #pragma unroll
     for (int q = 0; q < 8; ++q)
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        if (e < N) out[q * N + e] = acc[q][e];
+        if (e < ne) out[q * ldw + e] = acc[q][e];
   }
 }
 
@@ -523,25 +653,29 @@ __global__ __launch_bounds__(256) void dwg_reduce_kernel(const float* __restrict
 
 template <typename T, int NE, int TOK>
 hipError_t run_router(const LayerDims& L, const T* x, const T* Wg, const float* bias, const RoutingPtrs& R,
-                      int32_t* blockhist, hipStream_t s) {
+                      int32_t* blockhist, const GateExtPtrs* G, hipStream_t s) {
   const int nb = (L.T + TPB - 1) / TPB;
-  hipLaunchKernelGGL((router_kernel<T, NE, TOK>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d, L.N, L.k,
-                     R.topk_idx, R.topk_w, blockhist);
+  if (G)  // two accumulator sets: half the tokens per pass keeps them in registers
+    hipLaunchKernelGGL((router_kernel<T, NE, (TOK > 1 ? TOK / 2 : 1), true>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d,
+                       L.N, L.k, R.topk_idx, R.topk_w, blockhist, *G);
+  else
+    hipLaunchKernelGGL((router_kernel<T, NE, TOK, false>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d,
+                       L.N, L.k, R.topk_idx, R.topk_w, blockhist, GateExtPtrs{});
   return hipGetLastError();
 }
 
 template <typename T>
 hipError_t route_typed(const LayerDims& L, const void* xv, const void* Wgv, const float* bias, const RoutingPtrs& R,
-                       int32_t* blockhist, void* Xpv, hipStream_t s) {
+                       int32_t* blockhist, void* Xpv, const GateExtPtrs* G, hipStream_t s) {
   const T* x = static_cast<const T*>(xv);
   const T* Wg = static_cast<const T*>(Wgv);
   hipError_t e;
-  if (L.N <= 2) e = run_router<T, 2, 4>(L, x, Wg, bias, R, blockhist, s);
-  else if (L.N <= 4) e = run_router<T, 4, 4>(L, x, Wg, bias, R, blockhist, s);
-  else if (L.N <= 8) e = run_router<T, 8, 2>(L, x, Wg, bias, R, blockhist, s);
-  else if (L.N <= 16) e = run_router<T, 16, 1>(L, x, Wg, bias, R, blockhist, s);
-  else if (L.N <= 32) e = run_router<T, 32, 1>(L, x, Wg, bias, R, blockhist, s);
-  else e = run_router<T, 64, 1>(L, x, Wg, bias, R, blockhist, s);
+  if (L.N <= 2) e = run_router<T, 2, 4>(L, x, Wg, bias, R, blockhist, G, s);
+  else if (L.N <= 4) e = run_router<T, 4, 4>(L, x, Wg, bias, R, blockhist, G, s);
+  else if (L.N <= 8) e = run_router<T, 8, 2>(L, x, Wg, bias, R, blockhist, G, s);
+  else if (L.N <= 16) e = run_router<T, 16, 1>(L, x, Wg, bias, R, blockhist, G, s);
+  else if (L.N <= 32) e = run_router<T, 32, 1>(L, x, Wg, bias, R, blockhist, G, s);
+  else e = run_router<T, 64, 1>(L, x, Wg, bias, R, blockhist, G, s);
   if (e != hipSuccess) return e;
   const int nb = (L.T + TPB - 1) / TPB;
   hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(256), 0, s, blockhist, nb, L.N, R.counts, R.offsets,
@@ -549,15 +683,45 @@ hipError_t route_typed(const LayerDims& L, const void* xv, const void* Wgv, cons
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((scatter_kernel<T>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, L.T, L.d, L.N, L.k, R.topk_idx,
                      R.offsets, blockhist, R.row_of, R.src_of, static_cast<T*>(Xpv));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (G && G->probs) {
+    hipLaunchKernelGGL(aux_finish_kernel, dim3(1), dim3(256), 0, s, G->probs, R.topk_idx, L.T, L.N, L.k, G->alpha,
+                       G->aux_f, G->aux_P, G->aux_loss);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+// dX and the gradient of one router-side matrix, 8 expert columns per launch
+template <typename T>
+hipError_t gate_rows_typed(const LayerDims& L, const void* x, const void* W, const void* dXp, const float* dl,
+                           const RoutingPtrs& R, int first, void* dX, float* partial, float* dW, int accumulate,
+                           hipStream_t s) {
+  const int nb = (L.T + BR_TOK - 1) / BR_TOK;
+  for (int e0 = 0; e0 < L.N; e0 += 8) {
+    hipLaunchKernelGGL((bwd_gate_rows_kernel<T>), dim3(nb), dim3(ROUTE_THREADS), 0, s, static_cast<const T*>(x),
+                       static_cast<const T*>(W), L.N, e0, min(8, L.N - e0), static_cast<const T*>(dXp), dl, L.T, L.d,
+                       L.k, R.row_of, (first && e0 == 0) ? 1 : 0, static_cast<T*>(dX), partial);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int n = L.d * L.N;
+  hipLaunchKernelGGL(dwg_reduce_kernel, dim3((n + 63) / 64), dim3(256), 0, s, partial, nb, n, accumulate, dW);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
-                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, hipStream_t s) {
-  return dt == MODSE_F32 ? route_typed<float>(L, x, W_gate, bias, R, blockhist, Xp, s)
-                         : route_typed<bf16_t>(L, x, W_gate, bias, R, blockhist, Xp, s);
+                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, const GateExtPtrs* G, hipStream_t s) {
+  return dt == MODSE_F32 ? route_typed<float>(L, x, W_gate, bias, R, blockhist, Xp, G, s)
+                         : route_typed<bf16_t>(L, x, W_gate, bias, R, blockhist, Xp, G, s);
+}
+
+hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,
+                                hipStream_t s) {
+  hipLaunchKernelGGL(routing_stats_kernel, dim3(1), dim3(256), 0, s, topk_idx, L.T, L.N, L.k, L, slot_counts, summary);
+  return hipGetLastError();
 }
 
 hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, const RoutingPtrs& R, void* y,
@@ -600,24 +764,25 @@ hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x,
 }
 
 hipError_t launch_bwd_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const void* dXp,
-                             const float* dg, const RoutingPtrs& R, void* dX, float* dWg_partial, float* dW_gate,
+                             const float* dg, const RoutingPtrs& R, const GateExtPtrs* G, float aux_grad,
+                             const BwdRouterBufs& B, void* dX, float* dW_gate, float* dW_noise, float* dgamma,
                              int accumulate, hipStream_t s) {
-  const bool small_n = L.N <= 8;
-  const int nb = small_n ? (L.T + BR_TOK - 1) / BR_TOK : (L.T + TPB - 1) / TPB;
-  if (dt == MODSE_F32) {
-    auto kern = small_n ? bwd_router8_kernel<float> : bwd_router_kernel<float>;
-    hipLaunchKernelGGL(kern, dim3(nb), dim3(ROUTE_THREADS), 0, s, static_cast<const float*>(x),
-                       static_cast<const float*>(W_gate), static_cast<const float*>(dXp), dg, L.T, L.d, L.N, L.k,
-                       R.topk_idx, R.topk_w, R.row_of, static_cast<float*>(dX), dWg_partial);
-  } else {
-    auto kern = small_n ? bwd_router8_kernel<bf16_t> : bwd_router_kernel<bf16_t>;
-    hipLaunchKernelGGL(kern, dim3(nb), dim3(ROUTE_THREADS), 0, s, static_cast<const bf16_t*>(x),
-                       static_cast<const bf16_t*>(W_gate), static_cast<const bf16_t*>(dXp), dg, L.T, L.d, L.N, L.k,
-                       R.topk_idx, R.topk_w, R.row_of, static_cast<bf16_t*>(dX), dWg_partial);
-  }
+  const GateExtPtrs none = {};
+  const GateExtPtrs& g = G ? *G : none;
+  const bool noise = g.W_noise != nullptr;
+  const float aux_coef = g.probs ? aux_grad * g.alpha * (float)L.N / (float)L.T : 0.f;
+  const int nbt = (L.T + 255) / 256;
+  hipLaunchKernelGGL(gate_bwd_kernel, dim3(nbt), dim3(256), 0, s, dg, L.T, L.N, L.k, R.topk_idx, R.topk_w, R.row_of, g,
+                     aux_coef, B.dl, noise ? B.du : nullptr, noise ? B.dgamma_part : nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int n = L.d * L.N;
-  hipLaunchKernelGGL(dwg_reduce_kernel, dim3((n + 63) / 64), dim3(256), 0, s, dWg_partial, nb, n, accumulate, dW_gate);
+  e = dt == MODSE_F32 ? gate_rows_typed<float>(L, x, W_gate, dXp, B.dl, R, 1, dX, B.dW_partial, dW_gate, accumulate, s)
+                      : gate_rows_typed<bf16_t>(L, x, W_gate, dXp, B.dl, R, 1, dX, B.dW_partial, dW_gate, accumulate, s);
+  if (e != hipSuccess || !noise) return e;
+  e = dt == MODSE_F32
+          ? gate_rows_typed<float>(L, x, g.W_noise, nullptr, B.du, R, 0, dX, B.dW_partial, dW_noise, accumulate, s)
+          : gate_rows_typed<bf16_t>(L, x, g.W_noise, nullptr, B.du, R, 0, dX, B.dW_partial, dW_noise, accumulate, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(dwg_reduce_kernel, dim3(1), dim3(256), 0, s, B.dgamma_part, nbt, 1, accumulate, dgamma);
   return hipGetLastError();
 }

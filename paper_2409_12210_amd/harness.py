@@ -59,6 +59,35 @@ class LayerRunner:
             self.dW3 = torch.zeros((self.F, self.d), **f32)
             self.dW2 = torch.zeros(self.d * self.F, **f32)
 
+    def enable_ext(self, W_noise=None, gamma=1.0, eps=1e-6, aux_alpha=None):
+        """Switch on the optional gate parts: the noise term (W_noise given) and/or the auxiliary loss
+        (aux_alpha given); allocates the buffers they need.  fwd / route / bwd then go through the *_ext calls."""
+        f32 = dict(dtype=torch.float32, device=self.device)
+        e = B.GateExt()
+        Tn = max(self.T, 1)
+        if W_noise is not None:
+            e.W_noise = to_device(W_noise, self.dtype, self.device)
+            e.gamma = torch.tensor([float(gamma)], **f32)
+            e.eps = float(eps)
+            e.noise_pre = torch.empty((Tn, self.N), **f32)
+            self.dW_noise = torch.zeros((self.d, self.N), **f32)
+            self.dgamma = torch.zeros(1, **f32)
+        if aux_alpha is not None:
+            e.aux_alpha = float(aux_alpha)
+            e.probs = torch.empty((Tn, self.N), **f32)
+            e.aux_f = torch.empty(self.N, **f32)
+            e.aux_P = torch.empty(self.N, **f32)
+            e.aux_loss = torch.empty(1, **f32)
+        self.ext = e
+        return e
+
+    def stats(self):
+        """slot_counts [k, N] and summary [k + 2] of the last routing (device tensors)."""
+        sc = torch.empty((self.k, self.N), dtype=torch.int32, device=self.device)
+        sm = torch.empty(self.k + 2, dtype=torch.float32, device=self.device)
+        B.modse_routing_stats(*self._args(), self.routing, sc, sm)
+        return sc, sm
+
     @classmethod
     def from_inputs(cls, inp, need_bwd=False, device="cuda"):
         c = inp.cfg
@@ -69,14 +98,28 @@ class LayerRunner:
         return (self.d, self.d_ff, self.k, self.dtype, self.T)
 
     def route(self):
-        B.modse_route(*self._args(), self.x, self.W_gate, self.bias, self.routing, self.ws)
+        if getattr(self, "ext", None) is not None:
+            B.modse_route_ext(*self._args(), self.x, self.W_gate, self.bias, self.ext, self.routing, self.ws)
+        else:
+            B.modse_route(*self._args(), self.x, self.W_gate, self.bias, self.routing, self.ws)
 
     def fwd(self, with_routing=True, save=None):
         save = self.need_bwd if save is None else save
+        if getattr(self, "ext", None) is not None:
+            B.modse_layer_fwd_ext(*self._args(), self.x, self.W_gate, self.bias, self.ext, self.W1, self.W3, self.W2,
+                                  self.y, self.routing if with_routing else None, self.saved if save else None,
+                                  self.ws)
+            return
         B.modse_layer_fwd(*self._args(), self.x, self.W_gate, self.bias, self.W1, self.W3, self.W2, self.y,
                           self.routing if with_routing else None, self.saved if save else None, self.ws)
 
-    def bwd(self, accumulate=False):
+    def bwd(self, accumulate=False, aux_grad=1.0):
+        if getattr(self, "ext", None) is not None:
+            B.modse_layer_bwd_ext(*self._args(), self.x, self.W_gate, self.ext, aux_grad, self.W1, self.W3, self.W2,
+                                  self.routing, self.saved, self.dY, self.dX, self.dW_gate,
+                                  getattr(self, "dW_noise", None), getattr(self, "dgamma", None), self.dW1, self.dW3,
+                                  self.dW2, accumulate, self.ws)
+            return
         B.modse_layer_bwd(*self._args(), self.x, self.W_gate, self.W1, self.W3, self.W2, self.routing, self.saved,
                           self.dY, self.dX, self.dW_gate, self.dW1, self.dW3, self.dW2, accumulate, self.ws)
 

@@ -95,3 +95,32 @@ def test_zero_tokens_is_a_noop():
     a = (C0["d_model"], C0["d_ff"], C0["top_k"], C0["dtype"], 0)
     assert m.modse_layer_fwd(*a, None, None, None, None, None, None, None, None, None, None, ws_bytes=0, stream=0,
                              raise_on_error=False) == OK
+
+
+def test_gate_extension_argument_checks():
+    a = (C0["d_model"], C0["d_ff"], C0["top_k"], C0["dtype"], 16)
+    fake = 0x1000
+    r = m.Routing(fake, fake, fake, fake, fake, fake, fake)
+    # a switched-on part with a missing pointer is rejected before the workspace is looked at
+    noise_no_gamma = m.GateExt(W_noise=fake, gamma=None, eps=1e-6, noise_pre=fake)
+    assert m.modse_route_ext(*a, fake, fake, None, noise_no_gamma, r, fake, ws_bytes=1 << 30, stream=0,
+                             raise_on_error=False) == INVALID
+    aux_no_loss = m.GateExt(aux_alpha=0.01, probs=fake, aux_f=fake, aux_P=fake, aux_loss=None)
+    assert m.modse_layer_fwd_ext(*a, fake, fake, None, aux_no_loss, fake, fake, fake, fake, None, None, fake,
+                                 ws_bytes=1 << 30, stream=0, raise_on_error=False) == INVALID
+    neg_eps = m.GateExt(W_noise=fake, gamma=fake, eps=-1.0, noise_pre=fake)
+    assert m.modse_route_ext(*a, fake, fake, None, neg_eps, r, fake, ws_bytes=1 << 30, stream=0,
+                             raise_on_error=False) == INVALID
+    # complete extensions pass the checks and fail on the (deliberately) small workspace
+    full = m.GateExt(W_noise=fake, gamma=fake, eps=1e-6, noise_pre=fake, aux_alpha=0.01, probs=fake, aux_f=fake,
+                     aux_P=fake, aux_loss=fake)
+    assert m.modse_route_ext(*a, fake, fake, None, full, r, fake, ws_bytes=16, stream=0,
+                             raise_on_error=False) == WORKSPACE
+    # backward with the noise term needs somewhere to put dW_noise and dgamma
+    assert m.modse_layer_bwd_ext(*a, fake, fake, full, 1.0, fake, fake, fake, r, fake, fake, fake, fake, None, None,
+                                 fake, fake, fake, 0, fake, ws_bytes=1 << 30, stream=0,
+                                 raise_on_error=False) == INVALID
+    assert m.modse_layer_bwd_ext(*a, fake, fake, full, 1.0, fake, fake, fake, r, fake, fake, fake, fake, fake, fake,
+                                 fake, fake, fake, 0, fake, ws_bytes=16, stream=0, raise_on_error=False) == WORKSPACE
+    assert m.modse_routing_stats(*a, r, None, fake, stream=0, raise_on_error=False) == INVALID
+    assert m.modse_routing_stats(*a, None, fake, fake, stream=0, raise_on_error=False) == INVALID

@@ -23,7 +23,7 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-TENSOR_IDS = {"x": 1, "W_gate": 2, "W1": 3, "W3": 4, "W2": 5, "dY": 6}
+TENSOR_IDS = {"x": 1, "W_gate": 2, "W1": 3, "W3": 4, "W2": 5, "dY": 6, "W_noise": 7}
 
 
 @dataclass(frozen=True)
@@ -140,6 +140,11 @@ def make_inputs(cfg: LayerConfig, need_dy: bool = False, logit_bias=None) -> Lay
     dY = _normal(cfg.dy_seed, "dY", (T, d), 1.0, cfg.dtype) if need_dy else None
     lb = None if logit_bias is None else np.ascontiguousarray(logit_bias, dtype=np.float32)
     return LayerInputs(cfg, x, Wg, W1, W3, W2, dY, lb, expert_offsets(cfg.d_ff))
+
+
+def make_noise_weights(cfg: LayerConfig, sigma: float = 0.02) -> np.ndarray:
+    """W_noise [d, N] of the optional noise term of the gate, drawn like the other weights (own stream)."""
+    return _normal(cfg.seed, "W_noise", (cfg.d_model, cfg.n_experts), sigma, cfg.dtype)
 
 
 def zipf_target_shares(d_ff, s: float) -> np.ndarray:
