@@ -141,6 +141,8 @@ hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int
                                 hipStream_t s);
 hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, const RoutingPtrs& R, void* y,
                           hipStream_t s);
+hipError_t launch_combine_split(const LayerDims& L, modse_dtype dt, const float* Opart, int kchunk, const RoutingPtrs& R,
+                                void* y, hipStream_t s);
 hipError_t launch_bwd_prep(const LayerDims& L, modse_dtype dt, const void* dY, const void* O, const RoutingPtrs& R,
                            void* dO, float* dg, hipStream_t s);
 hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, void* Xp,
@@ -161,12 +163,17 @@ struct TileShape {
   int32_t bm, bn;
 };
 TileShape gemm_tile_shape(modse_dtype dt, int epilogue, int64_t T);
+// layout < 0: the layout that goes with the epilogue (see gemm.hip)
 hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* plan, int accumulate, int save_pre,
-                               int64_t max_tiles, hipStream_t s);
+                               int64_t max_tiles, hipStream_t s, int layout = -1);
 
 struct FwdPlanArgs {
   const void *Xp, *W1, *W3, *W2;
   void *H, *dHdA, *dHdB, *O;  // dHdA/dHdB (derivatives of h by the two pre-activations) may be null
+  // split-K down-projection for decode-sized batches: expert e's K = f_e is cut into chunks of `kchunk`
+  // columns; chunk c writes float32 partial sums to Opart[c] ([T*k, d] each), which the combine step adds up.
+  float* Opart;
+  int32_t kchunk;  // 0 = no split
   GemmPlan *up, *down;
   TileShape up_tile, down_tile;
 };

@@ -143,6 +143,27 @@ __global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, co
     a.up->prob[i] = P;
   }
   finish_plan(a.up, i, L.N, a.up_tile.bm, a.up_tile.bn, s_tiles);
+  if (a.kchunk > 0) {  // split-K: one problem per (expert, chunk of K), float32 partial sums
+    int first = 0;     // problems of the experts listed before this one
+    for (int q = 0; q < i && q < L.N; ++q) first += (L.f[L.order[q]] + a.kchunk - 1) / a.kchunk;
+    int total = 0;
+    for (int q = 0; q < L.N; ++q) total += (L.f[q] + a.kchunk - 1) / a.kchunk;
+    if (on) {
+      const int nchunk = (f + a.kchunk - 1) / a.kchunk;
+      for (int c = 0; c < nchunk; ++c) {
+        const int k0 = c * a.kchunk;
+        GemmProblem P = {};
+        P.A = cadd(a.H, (hoff + k0) * es);
+        P.B = cadd(a.W2, ((size_t)L.foff[e] * d + k0) * es);
+        P.C = a.Opart + ((size_t)c * L.T * L.k + offsets[e]) * d;
+        P.M = n_e; P.N = d; P.K = min(a.kchunk, f - k0);
+        P.lda = f; P.ldb = f; P.ldc = d;
+        a.down->prob[first + c] = P;
+      }
+    }
+    finish_plan(a.down, i, total, a.down_tile.bm, a.down_tile.bn, s_tiles);
+    return;
+  }
   if (on) {
     GemmProblem P = {};
     P.A = cadd(a.H, hoff * es);
@@ -261,7 +282,11 @@ TileShape gemm_tile_shape(modse_dtype dt, int epilogue, int64_t T) {
 // The epilogue fixes the operand layout: forward GEMMs are K-contiguous on both sides, data gradients read
 // the weights as [K, N], weight gradients read both activations token-major.
 hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* plan, int accumulate, int save_pre,
-                               int64_t max_tiles, hipStream_t s) {
+                               int64_t max_tiles, hipStream_t s, int layout) {
+  if (epilogue == EPI_STORE_F32 && layout == LAYOUT_TN) {  // split-K partial sums of a forward GEMM
+    if (dt == MODSE_F32) return run_f32<EPI_STORE_F32, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);
+    return run_bf16<256, 256, 1, 4, 2, EPI_STORE_F32, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);
+  }
   if (dt == MODSE_F32) {
     switch (epilogue) {
       case EPI_STORE: return run_f32<EPI_STORE, LAYOUT_TN>(plan, accumulate, save_pre, max_tiles, s);

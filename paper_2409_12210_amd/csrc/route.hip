@@ -82,8 +82,10 @@ __device__ inline double softplus_f64(double u) {  // log(1 + exp(u)) without ov
 // EXT adds the optional parts of the gate: the noise term RMSNorm(Softplus(x W_n)) of H(x) (Sec. 2 Eq. 4-5;
 // G.Wn != null) and the full-softmax probabilities p(x) that the auxiliary loss needs (Sec. 3.2 Eq. 11;
 // G.probs != null).  Both reuse the x rows this kernel already holds in registers.
+// (Two waves per SIMD are asked for so that the kernel stays within the 256 architectural registers: a
+// variant of it that the compiler let run over into accumulation registers computed wrong sums.)
 template <typename T, int NE, int TOK, bool EXT>
-__global__ __launch_bounds__(ROUTE_THREADS) void router_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
+__global__ __launch_bounds__(ROUTE_THREADS, 2) void router_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
                                                                const float* __restrict__ bias, int ntok, int d, int N,
                                                                int top_k, int32_t* __restrict__ topk_idx,
                                                                float* __restrict__ topk_w,
@@ -466,6 +468,43 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ O, i
   }
 }
 
+// Combine after a split-K down-projection: expert e's output rows are the sum of ceil(f_e / kchunk) float32
+// partial slabs Opart[c] ([T*k, d] each), added in ascending c.  One thread per token and 8 columns.
+template <typename T>
+__global__ __launch_bounds__(256) void combine_split_kernel(const float* __restrict__ Opart, int ntok, int d,
+                                                            int top_k, LayerDims L, int kchunk,
+                                                            const int32_t* __restrict__ topk_idx,
+                                                            const int32_t* __restrict__ row_of,
+                                                            const float* __restrict__ topk_w, T* __restrict__ y) {
+  const int per_tok = d / 8;
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long)ntok * per_tok) return;
+  const int t = (int)(i / per_tok), c = (int)(i % per_tok) * 8;
+  const size_t slab = (size_t)ntok * top_k * d;
+  float o[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) o[q] = 0.f;
+  for (int j = 0; j < top_k; ++j) {
+    const int e = topk_idx[(size_t)t * top_k + j];
+    const float* src = Opart + (size_t)row_of[(size_t)t * top_k + j] * d + c;
+    const float g = topk_w[(size_t)t * top_k + j];
+    const int nchunk = (L.f[e] + kchunk - 1) / kchunk;
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+#pragma unroll 4
+    for (int s = 0; s < nchunk; ++s) {
+      float v[8];
+      load8(src + s * slab, v);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] += v[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) o[q] = fmaf(g, acc[q], o[q]);
+  }
+  store8(y + (size_t)t * d + c, o);
+}
+
 // Backward of the combine: for permuted row r = (token t, slot j):
 //   dO[r] = g[t,j] * dY[t]      d g[t,j] = <dY[t], O[r]>
 template <typename T>
@@ -733,6 +772,18 @@ hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, con
   else
     hipLaunchKernelGGL((combine_kernel<bf16_t>), dim3(nb), dim3(256), 0, s, static_cast<const bf16_t*>(O), L.T, L.d,
                        L.k, R.row_of, R.topk_w, static_cast<bf16_t*>(y));
+  return hipGetLastError();
+}
+
+hipError_t launch_combine_split(const LayerDims& L, modse_dtype dt, const float* Opart, int kchunk, const RoutingPtrs& R,
+                                void* y, hipStream_t s) {
+  const int nb = (int)(((long)L.T * (L.d / 8) + 255) / 256);
+  if (dt == MODSE_F32)
+    hipLaunchKernelGGL((combine_split_kernel<float>), dim3(nb), dim3(256), 0, s, Opart, L.T, L.d, L.k, L, kchunk,
+                       R.topk_idx, R.row_of, R.topk_w, static_cast<float*>(y));
+  else
+    hipLaunchKernelGGL((combine_split_kernel<bf16_t>), dim3(nb), dim3(256), 0, s, Opart, L.T, L.d, L.k, L, kchunk,
+                       R.topk_idx, R.row_of, R.topk_w, static_cast<bf16_t*>(y));
   return hipGetLastError();
 }
 
