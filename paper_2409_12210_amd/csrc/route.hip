@@ -604,7 +604,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(const float* __restrict__
 //   partial[b] = sum_{t in block} x[t] (outer) dl[t, e0 : e0+ne]      (reduced over blocks by dwg_reduce_kernel)
 // A thread owns 8 columns of d for all tokens of the block, keeps the 8 x 8 slice of W and of the partial in
 // registers, and per token reads x and the dXp rows once (16-byte loads, a full row per block instruction).
-constexpr int BR_TOK = 64;
+constexpr int BR_TOK = 32;
 template <typename T>
 __global__ __launch_bounds__(ROUTE_THREADS) void bwd_gate_rows_kernel(
     const T* __restrict__ x, const T* __restrict__ W, int ldw, int e0, int ne, const T* __restrict__ dXp,
@@ -635,7 +635,8 @@ __global__ __launch_bounds__(ROUTE_THREADS) void bwd_gate_rows_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
     }
-    for (int tl = 0; tl < nt; ++tl) {
+#pragma unroll 4
+    for (int tl = 0; tl < nt; ++tl) {  // unrolled so that the loads of several tokens are in flight together
       const int t = t0 + tl;
       float dlv[8], xv[8], a[8], o[8];
       load8(&s_dl[tl][0], dlv);
