@@ -115,3 +115,40 @@ def test_c4_training_step_full_size():
         worst["dW2"] = max(worst["dW2"], max_rel(dW2[d * foff[e]:d * foff[e + 1]].reshape(d, f)[:, cols], g2))
     for name, err in worst.items():
         assert err <= tol, (name, err)
+
+
+def test_c1_gate_extensions_and_statistics_full_size():
+    """Router with the noise term and the auxiliary loss at the 16K-token configuration, and the routing
+    statistics of the plain router: all cheap enough for the oracle to do in full."""
+    import torch
+    from paper_2409_12210_amd.harness import LayerRunner, to_host
+    cfg = wl.CONFIGS["C1"]
+    inp = wl.make_inputs(cfg)
+    T, k, N = cfg.n_tokens, cfg.top_k, cfg.n_experts
+    Wn = wl.make_noise_weights(cfg)
+    gamma, eps, alpha = 0.5, 1e-6, 0.01
+    r = LayerRunner.from_inputs(inp)
+    r.enable_ext(W_noise=Wn, gamma=gamma, eps=eps, aux_alpha=alpha)
+    r.route()
+    got = r.routing_host()
+    on = orc.Noise(Wn, gamma, eps)
+    ref = orc.route(inp.x, inp.W_gate, N, k, None, on)
+    near = orc.near_tie_mask(ref.logits, k)
+    assert (got["topk_idx"][~near] == ref.topk_idx[~near]).all()
+    assert np.abs(got["topk_w"][~near] - ref.topk_w[~near]).max() < 2e-7
+    counts, offsets, row_of, src_of = orc.permutation_from_indices(got["topk_idx"], N)
+    assert (got["counts"] == counts).all() and (got["row_of"] == row_of).all()
+    L, f, P, p = orc.aux_loss(ref.logits, alpha)
+    assert max_rel(to_host(r.ext.probs), p) < 1e-5
+    assert max_rel(to_host(r.ext.noise_pre), orc.noise_term(inp.x, on)[1]) < 1e-5
+    assert np.abs(to_host(r.ext.aux_f) - np.bincount(got["topk_idx"][:, 0], minlength=N) / T).max() < 1e-7
+    assert max_rel(to_host(r.ext.aux_P), P) < 1e-5
+    assert abs(float(to_host(r.ext.aux_loss)[0]) - L) < 1e-4 * L
+    # statistics of this routing
+    sc, sm = r.stats()
+    torch.cuda.synchronize()
+    st = orc.routing_stats(got["topk_idx"], cfg.d_ff)
+    assert (to_host(sc) == st.slot_counts).all()
+    sm = to_host(sm)
+    assert np.allclose(sm[:k], st.slot_ratio, rtol=1e-5)
+    assert abs(sm[k] - st.total_ratio) < 1e-5 * st.total_ratio and abs(sm[k + 1] - st.avg_hidden) < 1e-5 * st.avg_hidden
