@@ -76,8 +76,8 @@ def main():
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path is single-GPU; see DESIGN.md for how it "
-              "would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the layer's hot path is single-GPU; sharding over "
+              "several GPUs is a design note, not code); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
