@@ -151,6 +151,19 @@ def main():
     extra = {"fwd_grouped_gemm_tflops": round(fwd_gemm_tflops, 2),
              "fwd_grouped_gemm_frac_of_bf16_peak": round(fwd_gemm_tflops / PEAK_BF16_TFLOPS, 4),
              "down_gemm_tflops": round(down_flops / (stages["down"] * 1e-3) / 1e12, 2) if stages["down"] > 0 else 0}
+    # HBM-bound stages: algorithmic bytes (each tensor counted once per kernel that must touch it) over stage time
+    b = 2 if cfg.dtype == "bf16" else 4
+    k = cfg.top_k
+    hbm_bytes = {
+        # router reads x; scatter reads x again and writes the k permuted copies; routing arrays are noise
+        "route": T * d * b + (T * d * b + k * T * d * b) + 40 * T,
+        "combine": k * T * d * b + T * d * b,
+    }
+    if bwd:
+        hbm_bytes["bwd_prep"] = (T * d * b + k * T * d * b) + 3 * k * T * d * b      # gather Xp; dY, O -> dO, dg
+        hbm_bytes["bwd_router"] = T * d * b + k * T * d * b + T * d * b               # x, dXp rows -> dX (+ dW_gate)
+    extra["hbm_stage_gbs"] = {s: round(v / (stages[s] * 1e-3) / 1e9, 1) for s, v in hbm_bytes.items() if stages[s] > 0}
+    extra["hbm_stage_frac_of_peak"] = {s: round(v / PEAK_HBM_GBS, 3) for s, v in extra["hbm_stage_gbs"].items()}
     if bwd:
         dgrad_ms, wgrad_ms = stages["bwd_dgrad"], stages["bwd_wgrad"]
         if dgrad_ms > 0:

@@ -624,52 +624,68 @@ __global__ __launch_bounds__(ROUTE_THREADS) void bwd_gate_rows_kernel(
   const int nt = min(BR_TOK, ntok - t0);
   for (int c = tid * 8; c < d; c += ROUTE_THREADS * 8) {
     float wg[8][8], acc[8][8];
+    if (ldw == 8) {  // whole rows: eight 16-byte loads in flight together
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      if (ldw == 8) {
-        load8(W + (size_t)(c + q) * 8, wg[q]);
-      } else {
+      for (int q = 0; q < 8; ++q) load8(W + (size_t)(c + q) * 8, wg[q]);
+    } else {  // columns beyond ne repeat the last one and are zeroed afterwards (no branch per element)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) wg[q][e] = e < ne ? (float)W[(size_t)(c + q) * ldw + e0 + e] : 0.f;
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
-    }
-#pragma unroll 4
-    for (int tl = 0; tl < nt; ++tl) {  // unrolled so that the loads of several tokens are in flight together
-      const int t = t0 + tl;
-      float dlv[8], xv[8], a[8], o[8];
-      load8(&s_dl[tl][0], dlv);
-      load8(x + (size_t)t * d + c, xv);
-      if (first) {
-        load8(dXp + (size_t)s_row[tl][0] * d + c, a);
-        if (top_k == 2) {
-          float b[8];
-          load8(dXp + (size_t)s_row[tl][1] * d + c, b);
-#pragma unroll
-          for (int q = 0; q < 8; ++q) a[q] += b[q];
-        }
-      } else {
-        load8(dX + (size_t)t * d + c, a);
-      }
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        float go = a[q];
+      for (int q = 0; q < 8; ++q)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          go = fmaf(wg[q][e], dlv[e], go);
-          acc[q][e] = fmaf(xv[q], dlv[e], acc[q][e]);
+          const float w = (float)W[(size_t)(c + q) * ldw + e0 + min(e, ne - 1)];
+          wg[q][e] = e < ne ? w : 0.f;
         }
-        o[q] = go;
-      }
-      store8(dX + (size_t)t * d + c, o);
     }
-    float* out = partial + ((size_t)blockIdx.x * d + c) * ldw + e0;
 #pragma unroll
     for (int q = 0; q < 8; ++q)
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (e < ne) out[q * ldw + e] = acc[q][e];
+      for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
+    // four tokens at a time, all twelve row loads issued before any arithmetic (no branch between them: a
+    // missing second row is read from the first one's address and multiplied by zero)
+    const float use_b = (first && top_k == 2) ? 1.f : 0.f;
+    for (int tl0 = 0; tl0 < nt; tl0 += 4) {
+      float xv[4][8], av[4][8], bv[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int tl = min(tl0 + u, nt - 1);
+        const int t = t0 + tl;
+        const T* pa = first ? dXp + (size_t)s_row[tl][0] * d : dX + (size_t)t * d;
+        const T* pb = use_b != 0.f ? dXp + (size_t)s_row[tl][1] * d : pa;
+        load8(x + (size_t)t * d + c, xv[u]);
+        load8(pa + c, av[u]);
+        load8(pb + c, bv[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int tl = tl0 + u;
+        if (tl < nt) {
+          float dlv[8], o[8];
+          load8(&s_dl[tl][0], dlv);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            float go = fmaf(use_b, bv[u][q], av[u][q]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              go = fmaf(wg[q][e], dlv[e], go);
+              acc[q][e] = fmaf(xv[u][q], dlv[e], acc[q][e]);
+            }
+            o[q] = go;
+          }
+          store8(dX + (size_t)(t0 + tl) * d + c, o);
+        }
+      }
+    }
+    float* out = partial + ((size_t)blockIdx.x * d + c) * ldw + e0;
+    if (ldw == 8) {  // the thread's 8 x 8 block is 256 consecutive bytes
+#pragma unroll
+      for (int q = 0; q < 8; ++q) store8(out + q * 8, acc[q]);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (e < ne) out[q * ldw + e] = acc[q][e];
+    }
   }
 }
 
@@ -681,8 +697,10 @@ __global__ __launch_bounds__(256) void dwg_reduce_kernel(const float* __restrict
   const int li = threadIdx.x & 63, part = threadIdx.x >> 6;
   const int i = blockIdx.x * 64 + li;
   float acc = 0.f;
-  if (i < n)
-    for (int b = part; b < nb; b += 4) acc += partial[(size_t)b * n + i];
+  if (i < n) {
+#pragma unroll 8
+    for (int b = part; b < nb; b += 4) acc += partial[(size_t)b * n + i];  // unrolled: several loads in flight
+  }
   s_part[part][li] = acc;
   __syncthreads();
   if (part == 0 && i < n) {
