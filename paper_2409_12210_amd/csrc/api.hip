@@ -75,12 +75,12 @@ struct FwdLayout {
 // Decode-sized batches stream the expert weights once; the down-projection then has too few output tiles
 // to occupy the chip (d / 256 per expert) and very long K loops, so its K is cut into chunks that become
 // problems of their own.  Returns the chunk length (a multiple of 64), or 0 when K is not split.
-constexpr int64_t SPLITK_MAX_TOKENS = 64;
+constexpr int64_t SPLITK_MAX_TOKENS = MODSE_SKINNY_TOKENS;
 int splitk_chunk(const LayerDims& L) {
   if (L.T > SPLITK_MAX_TOKENS) return 0;
   int64_t F = 0;
   for (int e = 0; e < L.N; ++e) F += L.f[e];
-  const int64_t ntiles_n = (L.d + 255) / 256;
+  const int64_t ntiles_n = (L.d + 511) / 512;
   int64_t want = std::max<int64_t>(L.N, 1024 / ntiles_n);           // about four tiles per CU
   want = std::min<int64_t>(want, MODSE_MAX_PROBLEMS - L.N);          // sum_e ceil(f_e / chunk) <= want + N
   const int64_t chunk = align_up((size_t)((F + want - 1) / want), 64);
@@ -353,19 +353,21 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   HIP_TRY(launch_plan_fwd(L, dt, R.counts, R.offsets, pa, s));
   stamp.mark(MODSE_STAGE_PERMUTE);
 
-  HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU, pa.up, 0, saved != nullptr, tiles_bound(L, T, pa.up_tile, true), s));
+  const int skinny = T <= MODSE_SKINNY_TOKENS;
+  HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU, pa.up, 0, saved != nullptr, tiles_bound(L, T, pa.up_tile, true), s, -1,
+                              skinny));
   stamp.mark(MODSE_STAGE_UP);
   if (kchunk) {
     int64_t nprob = 0;
     for (int e = 0; e < L.N; ++e) nprob += (L.f[e] + kchunk - 1) / kchunk;
     const int64_t bound = nprob * ((T + pa.down_tile.bm - 1) / pa.down_tile.bm) * ((L.d + pa.down_tile.bn - 1) / pa.down_tile.bn);
-    HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.down, 0, 0, bound, s, LAYOUT_TN));
+    HIP_TRY(launch_grouped_gemm(dt, EPI_STORE_F32, pa.down, 0, 0, bound, s, LAYOUT_TN, skinny));
     stamp.mark(MODSE_STAGE_DOWN);
     HIP_TRY(launch_combine_split(L, dt, pa.Opart, kchunk, R, y, s));
     stamp.mark(MODSE_STAGE_COMBINE);
     return MODSE_OK;
   }
-  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE, pa.down, 0, 0, tiles_bound(L, T, pa.down_tile, false), s));
+  HIP_TRY(launch_grouped_gemm(dt, EPI_STORE, pa.down, 0, 0, tiles_bound(L, T, pa.down_tile, false), s, -1, skinny));
   stamp.mark(MODSE_STAGE_DOWN);
   HIP_TRY(launch_combine(L, dt, pa.O, R, y, s));
   stamp.mark(MODSE_STAGE_COMBINE);

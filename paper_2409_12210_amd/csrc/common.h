@@ -7,6 +7,7 @@
 
 #define MODSE_MAX_EXPERTS 64
 #define MODSE_MAX_PROBLEMS (3 * MODSE_MAX_EXPERTS)  // the three weight-gradient GEMMs share one launch
+#define MODSE_SKINNY_TOKENS 64           // batches up to this size take the decode-shaped forward GEMMs
 #define MODSE_ROUTE_TOKENS_PER_BLOCK 32  // tokens handled by one block of the router / scatter kernels
 
 typedef __bf16 bf16_t;
@@ -163,9 +164,10 @@ struct TileShape {
   int32_t bm, bn;
 };
 TileShape gemm_tile_shape(modse_dtype dt, int epilogue, int64_t T);
-// layout < 0: the layout that goes with the epilogue (see gemm.hip)
+// layout < 0: the layout that goes with the epilogue (see gemm.hip); skinny: the plan was made with the
+// decode-sized tile shapes of gemm_tile_shape (every problem has M <= MODSE_SKINNY_TOKENS)
 hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* plan, int accumulate, int save_pre,
-                               int64_t max_tiles, hipStream_t s, int layout = -1);
+                               int64_t max_tiles, hipStream_t s, int layout = -1, int skinny = 0);
 
 struct FwdPlanArgs {
   const void *Xp, *W1, *W3, *W2;

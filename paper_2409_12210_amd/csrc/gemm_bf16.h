@@ -76,8 +76,9 @@ struct Bf16Tile {
   static constexpr int UNITS = ROWS / 8;     // ... of the whole stage
   static constexpr int UPW = UNITS / NWAVES; // units per wave and stage
   static constexpr int STAGE = ROWS * 128;
-  static_assert(UNITS % NWAVES == 0 && UPW % 2 == 0, "load units must divide evenly among waves");
-  static_assert(UPW % MODSE_DMA_SPREAD == 0 && MODSE_DMA_SPREAD <= 4, "load slices");
+  static constexpr bool SKINNY = BM == 64;  // decode-sized M: every wave loads one A unit and UPW - 1 B units
+  static_assert(UNITS % NWAVES == 0 && (UPW % 2 == 0 || SKINNY), "load units must divide evenly among waves");
+  static_assert(MODSE_DMA_SPREAD == 2, "the stage loads go out in two slices");
   static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
 };
 
@@ -99,10 +100,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   using Cfg = Bf16Tile<BM, BN, NB, WAVES_M, WAVES_N>;
   constexpr int BK = Cfg::BK, MI = Cfg::MI, NI = Cfg::NI, UA = Cfg::UA, UPW = Cfg::UPW, STAGE = Cfg::STAGE;
   constexpr int WM = Cfg::WM, WN = Cfg::WN;
-  constexpr int SLICE = UPW / MODSE_DMA_SPREAD;
+  constexpr int SLICE0 = (UPW + 1) / 2;  // units of the first of the two load slices
+  constexpr bool SKINNY = Cfg::SKINNY;
   constexpr bool A_T = (LAYOUT & 1) != 0, B_T = (LAYOUT & 2) != 0;
+  static_assert(!SKINNY || (!A_T && !B_T && UA == Cfg::NWAVES && WAVES_M == 1), "skinny tiles: forward layouts, one A unit per wave");
   static_assert(!(A_T && BM != 256) && !(B_T && (BN != 256 || NB != 1)), "transposed operands use 256-wide tiles");
-  static_assert(UA % UPW == 0 && (BN / 8) % UPW == 0, "all load units of a wave must belong to one operand");
+  static_assert(SKINNY || (UA % UPW == 0 && (BN / 8) % UPW == 0), "all load units of a wave must belong to one operand");
   __shared__ __attribute__((aligned(1024))) char stages[2 * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -110,7 +113,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int total = plan->tile_start[plan->n_prob];
   const int first_tile = first_tile_of_block();
-  const uint32_t lds_mine = __builtin_amdgcn_readfirstlane(lds_address(stages)) + wave * UPW * 1024;
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(lds_address(stages));
+  // load unit (8 LDS rows) that this wave's i-th load of a stage fills.  Regular tiles: UPW consecutive units,
+  // all of one operand.  Skinny tiles: A unit `wave`, then UPW - 1 consecutive B units.
+  auto unit_of = [&](int i) -> int {
+    if (SKINNY) return i == 0 ? wave : UA + wave * (UPW - 1) + (i - 1);
+    return wave * UPW + i;
+  };
+  const int first_b_unit = SKINNY ? UA + wave * (UPW - 1) : wave * UPW;  // (meaningful when the wave loads B)
   const int lrow = lane >> 3;  // row inside a load unit
   // element offset of the chunk this lane fetches, for even and odd load units: LDS position (row, p)
   // holds logical chunk p ^ ((row >> 1) & 7), and row = 8 * unit + lrow
@@ -122,7 +132,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   const int khalf = lane >> 5, lsw = (lane >> 1) & 7;
   // transposed operands: this lane's row inside a load unit (2 rows of 32 chunks) and its chunk
   const int t_row = lane >> 5, t_chunk = lane & 31;
-  const bool loads_a = wave * UPW < UA;                       // wave-uniform: which operand this wave loads
+  const bool loads_a = !SKINNY && wave * UPW < UA;            // wave-uniform: which operand a regular wave loads
   const bool loads_t = loads_a ? A_T : B_T;                   // ... and whether it is a transposed one
 
   auto open_tile = [&](StepCursor& c) {
@@ -141,6 +151,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   // ---- issue side: runs one K step ahead of the MFMAs, across tile boundaries
   StepCursor ic;
   const char* ibase[2] = {nullptr, nullptr};  // operand this wave loads from, per pass of a dual-K product
+  const char* ibase_a = nullptr;              // skinny tiles: the A operand (unit 0 of every wave)
   int ikstride = 1;                           // elements between consecutive K of that operand
   uint32_t ioff[UPW];  // byte offset of this lane's chunk per load unit (K offset 0) from the operand base
   // tiles without K steps (an expert that received no token, in a weight-gradient GEMM) take no stage
@@ -153,8 +164,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   auto issue_offsets = [&]() {
     const GemmProblem* P = ic.gp;
     {  // operand this wave loads from (wave-uniform)
-      const int u = wave * UPW;
-      if (u < UA) {
+      const int u = first_b_unit;
+      if (SKINNY) ibase_a = static_cast<const char*>(P->A);
+      if (!SKINNY && u < UA) {
         ibase[0] = static_cast<const char*>(P->A);
         ibase[1] = static_cast<const char*>(P->A2);
       } else if (NB == 2) {
@@ -179,8 +191,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     }
 #pragma unroll
     for (int i = 0; i < UPW; ++i) {
-      const int u = wave * UPW + i;
-      const int lchunk = (i & 1) ? lchunk_odd : lchunk_even;  // UPW is even: unit parity = i parity
+      const int u = unit_of(i);
+      const int lchunk = (u & 1) ? lchunk_odd : lchunk_even;  // both operand regions start at an even unit
       if (u < UA) {
         ioff[i] = (uint32_t)(min(ic.m0 + u * 8 + lrow, PM - 1) * lda + lchunk) * 2u;
       } else {
@@ -194,25 +206,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     if (!ic.valid) return;
     const int pass = (EPI == EPI_STORE_DUALK && ic.step >= ic.nk) ? 1 : 0;
     const int k0 = (ic.step - pass * ic.nk) * BK;
-    const uint32_t dst = lds_mine + buf * STAGE;
+    const uint32_t dst = lds_base + buf * STAGE;
     const char* base = ibase[pass] + (size_t)k0 * ikstride * 2;
     if (k0 + BK <= ic.K) {
 #pragma unroll
-      for (int i = first; i < first + count; ++i) dma_b128_s(base, ioff[i], dst + i * 1024);
+      for (int i = first; i < first + count; ++i)
+        dma_b128_s((SKINNY && i == 0) ? ibase_a + (size_t)k0 * 2 : base, ioff[i], dst + unit_of(i) * 1024);
     } else if (loads_t) {  // partial last step: K rows beyond K read zeros
 #pragma unroll
       for (int i = first; i < first + count; ++i) {
         const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
         const char* src = base + ioff[i];
         if (k0 + 2 * ul + t_row >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
-        dma_b128(src, dst + i * 1024);
+        dma_b128(src, dst + unit_of(i) * 1024);
       }
     } else {  // last step of a pass when K % 64 != 0: chunks beyond K read zeros
 #pragma unroll
       for (int i = first; i < first + count; ++i) {
-        const char* src = base + ioff[i];
-        if (k0 + ((i & 1) ? lchunk_odd : lchunk_even) >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
-        dma_b128(src, dst + i * 1024);
+        const char* src = ((SKINNY && i == 0) ? ibase_a + (size_t)k0 * 2 : base) + ioff[i];
+        if (k0 + ((unit_of(i) & 1) ? lchunk_odd : lchunk_even) >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
+        dma_b128(src, dst + unit_of(i) * 1024);
       }
     }
   };
@@ -331,7 +344,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         load_frags(buf, kk + 1, (kk + 1) & 1);
         if (kk < MODSE_DMA_SPREAD) {  // the loads of stage g+1 go out in slices between the MFMA groups
           __builtin_amdgcn_sched_barrier(0);
-          issue_slice(nbuf, kk * SLICE, SLICE);
+          issue_slice(nbuf, kk == 0 ? 0 : SLICE0, kk == 0 ? SLICE0 : UPW - SLICE0);
           __builtin_amdgcn_sched_barrier(0);
         }
         mfma_block(kk & 1);
@@ -348,7 +361,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     // ---- epilogue.  For register group r of block (i, j) the lane holds columns n .. n+3 of row m.
     const GemmProblem& CP = *cc.gp;
     const int cM = CP.M, cN = CP.N, cld = CP.ldc;
-    if constexpr (EPI == EPI_STORE_F32) {
+    if constexpr (EPI == EPI_STORE_F32 || SKINNY) {  // (a skinny tile's output is a few rows: stored directly)
       const int mrow = cc.m0 + wm * WM + (lane & 31);
       const int ncol = cc.n0 + wn * WN + 4 * khalf;
 #pragma unroll
@@ -357,10 +370,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         for (int j = 0; j < NI; ++j)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            float a[4];
+            float a[4], b[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) a[q] = acc[0][i][j][r * 4 + q];
-            epilogue4<bf16_t, EPI>(CP, mrow + i * 32, ncol + j * 32 + r * 8, a, a, accumulate, save_pre);
+            for (int q = 0; q < 4; ++q) {
+              a[q] = acc[0][i][j][r * 4 + q];
+              b[q] = acc[NB - 1][i][j][r * 4 + q];
+            }
+            epilogue4<bf16_t, EPI>(CP, mrow + i * 32, ncol + j * 32 + r * 8, a, b, accumulate, save_pre);
           }
     } else {
       // 16-bit outputs go through LDS so that global memory sees whole 128-byte lines: the wave works in
@@ -370,7 +386,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       // no other wave is involved; LDS serves one wave's accesses in program order.
       static_assert(NI % 2 == 0 && UPW >= 8, "staged epilogue: 64-column units, 8 KiB of stage per wave");
       constexpr int NJP = NI / 2, NU = MI * NJP;
-      char* const slot0 = stages + ((g + 1) & 1) * STAGE + wave * UPW * 1024;
+      char* const slot0 = stages + ((g + 1) & 1) * STAGE + first_b_unit * 1024;
       char* const slot1 = slot0 + 4096;
       const int er = lane & 31, esw = (er >> 1) & 7;
       const int rrow = lane >> 3, rchunk = lane & 7;
