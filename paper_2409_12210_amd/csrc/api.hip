@@ -68,7 +68,7 @@ size_t hidden_elems_max(const LayerDims& L) {
 }
 
 struct FwdLayout {
-  size_t blockhist, topk_idx, topk_w, counts, offsets, row_of, src_of, near_tie, plan_up, plan_down, Xp, H, O, Opart,
+  size_t blockhist, near_flag, topk_idx, topk_w, counts, offsets, row_of, src_of, near_tie, plan_up, plan_down, Xp, H, O, Opart,
       total;
 };
 
@@ -98,6 +98,7 @@ FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
   const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k;
   const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
   w.blockhist = c.take(nb * (L.N + 1) * 4);
+  w.near_flag = c.take((size_t)std::min<int64_t>(L.T, MODSE_SKINNY_TOKENS) * 4);
   w.topk_idx = c.take(Tk * 4);
   w.topk_w = c.take(Tk * 4);
   w.counts = c.take(L.N * 4);
@@ -285,7 +286,7 @@ modse_status modse_route_ext(const modse_desc* desc, int64_t T, const void* x, c
   char* wsb = static_cast<char*>(ws);
   const RoutingPtrs R = routing_from(out, wsb, w);
   HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
-                       nullptr, ext ? &G : nullptr, s));
+                       reinterpret_cast<int32_t*>(wsb + w.near_flag), nullptr, ext ? &G : nullptr, s));
   return MODSE_OK;
 }
 
@@ -328,8 +329,8 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   Stamp stamp(0, s);
 
   void* Xp = wsb + w.Xp;
-  HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist), Xp,
-                       ext ? &G : nullptr, s));
+  HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
+                       reinterpret_cast<int32_t*>(wsb + w.near_flag), Xp, ext ? &G : nullptr, s));
   stamp.mark(MODSE_STAGE_ROUTE);  // routing and the row scatter share kernels; the scatter is counted here
 
   FwdPlanArgs pa;

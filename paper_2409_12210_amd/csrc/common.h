@@ -136,8 +136,10 @@ struct GateExtPtrs {
 
 // ---------------------------------------------------------------- launchers
 // route.hip
+// near_flag: [T] ints of workspace (used by the decode-sized path only)
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
-                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, const GateExtPtrs* G, hipStream_t s);
+                        const RoutingPtrs& R, int32_t* blockhist, int32_t* near_flag, void* Xp, const GateExtPtrs* G,
+                        hipStream_t s);
 hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,
                                 hipStream_t s);
 hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, const RoutingPtrs& R, void* y,

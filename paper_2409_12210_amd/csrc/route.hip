@@ -227,6 +227,99 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_kernel(const T* __res
   if (tid <= N) blockhist[(size_t)blockIdx.x * (N + 1) + tid] = s_hist[tid];
 }
 
+// Router for decode-sized batches: one block per token, the 256 threads split the d columns, so the whole
+// dot product is one or two rounds of memory latency instead of the serial passes of router_kernel.  Every
+// thread leaves its N float64 partial sums in LDS; thread e adds the 256 partials of expert e in thread
+// order (fixed, so the result does not depend on timing); thread 0 does top-k and gate.  The block
+// histograms that the permutation needs are made by route_hist_kernel from topk_idx and near_flag.
+template <typename T, int NE>
+__global__ __launch_bounds__(ROUTE_THREADS, 2) void router_token_kernel(const T* __restrict__ x,
+                                                                       const T* __restrict__ Wg,
+                                                                       const float* __restrict__ bias, int d, int N,
+                                                                       int top_k, int32_t* __restrict__ topk_idx,
+                                                                       float* __restrict__ topk_w,
+                                                                       int32_t* __restrict__ near_flag) {
+  __shared__ double s_part[ROUTE_THREADS][NE + 1];  // (+1: rows start in different banks)
+  __shared__ double s_logit[NE];
+  const int tid = threadIdx.x, t = blockIdx.x;
+  double acc[NE];
+#pragma unroll
+  for (int e = 0; e < NE; ++e) acc[e] = 0.0;
+  for (int c = tid * 8; c < d; c += ROUTE_THREADS * 8) {
+    float xv[8];
+    load8(x + (size_t)t * d + c, xv);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const T* wrow = Wg + (size_t)(c + i) * N;
+      float wf[NE];
+      if (N == NE) {
+        load_row<NE>(wrow, wf);
+      } else {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) wf[e] = (float)wrow[min(e, N - 1)];
+      }
+      const double xd = (double)xv[i];
+#pragma unroll
+      for (int e = 0; e < NE; ++e) acc[e] = fma(xd, (double)wf[e], acc[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < NE; ++e) s_part[tid][e] = acc[e];
+  __syncthreads();
+  if (tid < N) {
+    double sum = 0.0;
+    for (int i = 0; i < ROUTE_THREADS; ++i) sum += s_part[i][tid];
+    s_logit[tid] = sum + (bias ? (double)bias[tid] : 0.0);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double m1 = -INFINITY, m2 = -INFINITY, m3 = -INFINITY;
+    int i1 = 0, i2 = 0;
+    for (int e = 0; e < N; ++e) {
+      const double l = s_logit[e];
+      if (l > m1) {  // strict comparisons while scanning upward: ties stay with the lower index
+        m3 = m2; m2 = m1; i2 = i1; m1 = l; i1 = e;
+      } else if (l > m2) {
+        m3 = m2; m2 = l; i2 = e;
+      } else if (l > m3) {
+        m3 = l;
+      }
+    }
+    bool near;
+    if (top_k == 2) {
+      const double g1 = 1.0 / (1.0 + exp(m2 - m1));  // softmax over the two kept logits
+      topk_idx[(size_t)t * 2] = i1;
+      topk_idx[(size_t)t * 2 + 1] = i2;
+      topk_w[(size_t)t * 2] = (float)g1;
+      topk_w[(size_t)t * 2 + 1] = (float)(1.0 - g1);
+      near = (m1 - m2 < 1e-6) || (N > 2 && m2 - m3 < 1e-6);
+    } else {
+      topk_idx[t] = i1;
+      topk_w[t] = 1.f;
+      near = (N > 1 && m1 - m2 < 1e-6);
+    }
+    near_flag[t] = near ? 1 : 0;
+  }
+}
+
+// blockhist[b][0..N-1] = assignments per expert among the TPB tokens of block b, blockhist[b][N] = its
+// near-tie token count (integer atomics in LDS: the result does not depend on their order).
+__global__ __launch_bounds__(64) void route_hist_kernel(const int32_t* __restrict__ topk_idx,
+                                                        const int32_t* __restrict__ near_flag, int ntok, int N,
+                                                        int top_k, int32_t* __restrict__ blockhist) {
+  __shared__ int s_hist[MODSE_MAX_EXPERTS + 1];
+  const int tid = threadIdx.x;
+  for (int i = tid; i <= N; i += 64) s_hist[i] = 0;
+  __syncthreads();
+  const int t = blockIdx.x * TPB + tid;
+  if (tid < TPB && t < ntok) {
+    for (int j = 0; j < top_k; ++j) atomicAdd(&s_hist[topk_idx[(size_t)t * top_k + j]], 1);
+    if (near_flag[t]) atomicAdd(&s_hist[N], 1);
+  }
+  __syncthreads();
+  for (int i = tid; i <= N; i += 64) blockhist[(size_t)blockIdx.x * (N + 1) + i] = s_hist[i];
+}
+
 // Single block.  Turns blockhist[b][e] into the exclusive prefix over blocks (in place) and writes
 // counts, offsets and the near-tie total.  Each thread owns a contiguous run of blocks; the 256 run totals
 // of one expert are scanned by the first wave.
@@ -724,10 +817,21 @@ hipError_t run_router(const LayerDims& L, const T* x, const T* Wg, const float* 
 
 template <typename T>
 hipError_t route_typed(const LayerDims& L, const void* xv, const void* Wgv, const float* bias, const RoutingPtrs& R,
-                       int32_t* blockhist, void* Xpv, const GateExtPtrs* G, hipStream_t s) {
+                       int32_t* blockhist, int32_t* near_flag, void* Xpv, const GateExtPtrs* G, hipStream_t s) {
   const T* x = static_cast<const T*>(xv);
   const T* Wg = static_cast<const T*>(Wgv);
   hipError_t e;
+  if (!G && near_flag && L.T <= MODSE_SKINNY_TOKENS && L.N <= 16) {  // decode-sized batch: one block per token
+    const dim3 grid(L.T), blk(ROUTE_THREADS);
+    if (L.N <= 2) hipLaunchKernelGGL((router_token_kernel<T, 2>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
+    else if (L.N <= 4) hipLaunchKernelGGL((router_token_kernel<T, 4>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
+    else if (L.N <= 8) hipLaunchKernelGGL((router_token_kernel<T, 8>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
+    else hipLaunchKernelGGL((router_token_kernel<T, 16>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(route_hist_kernel, dim3((L.T + TPB - 1) / TPB), dim3(64), 0, s, R.topk_idx, near_flag, L.T, L.N,
+                       L.k, blockhist);
+    e = hipGetLastError();
+  } else
   if (L.N <= 2) e = run_router<T, 2, 4>(L, x, Wg, bias, R, blockhist, G, s);
   else if (L.N <= 4) e = run_router<T, 4, 4>(L, x, Wg, bias, R, blockhist, G, s);
   else if (L.N <= 8) e = run_router<T, 8, 2>(L, x, Wg, bias, R, blockhist, G, s);
@@ -771,9 +875,10 @@ hipError_t gate_rows_typed(const LayerDims& L, const void* x, const void* W, con
 }  // namespace
 
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
-                        const RoutingPtrs& R, int32_t* blockhist, void* Xp, const GateExtPtrs* G, hipStream_t s) {
-  return dt == MODSE_F32 ? route_typed<float>(L, x, W_gate, bias, R, blockhist, Xp, G, s)
-                         : route_typed<bf16_t>(L, x, W_gate, bias, R, blockhist, Xp, G, s);
+                        const RoutingPtrs& R, int32_t* blockhist, int32_t* near_flag, void* Xp, const GateExtPtrs* G,
+                        hipStream_t s) {
+  return dt == MODSE_F32 ? route_typed<float>(L, x, W_gate, bias, R, blockhist, near_flag, Xp, G, s)
+                         : route_typed<bf16_t>(L, x, W_gate, bias, R, blockhist, near_flag, Xp, G, s);
 }
 
 hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,

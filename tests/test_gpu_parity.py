@@ -61,6 +61,11 @@ ROUTE_CASES = [
     ("n3", 96, (32, 64, 96), 130, "bf16", 2),
     ("n64", 64, (32,) * 64, 200, "f32", 2),
     ("wide_d", 4096, (64, 192, 128, 128), 70, "bf16", 2),
+    # decode-sized batches (at most 64 tokens) take the one-block-per-token router
+    ("decode_n16", 128, (64,) * 16, 40, "f32", 2),
+    ("decode_n3", 96, (32, 64, 96), 64, "bf16", 2),
+    ("decode_top1", 256, (128, 384, 192, 320), 33, "bf16", 1),
+    ("decode_wide", 4096, (64, 192, 128, 128, 64, 192, 128, 128), 64, "bf16", 2),
 ]
 
 
@@ -103,6 +108,11 @@ FWD_CASES = [
     ("bf16_tails", 320, (32, 608, 288, 352), 1531, "bf16", 2),
     ("bf16_top1", 256, (128, 384, 192, 320), 300, "bf16", 1),
     ("bf16_one_token", 256, (128, 384), 1, "bf16", 2),
+    # decode-sized batches: 64-row tiles and a split-K down-projection (ragged widths, chunk tails)
+    ("bf16_decode", 512, (96, 416, 160, 352, 224, 288, 256, 256), 64, "bf16", 2),
+    ("bf16_decode_17", 320, (32, 608, 288, 352), 17, "bf16", 2),
+    ("bf16_decode_long_k", 256, (2080, 64, 1056, 992), 30, "bf16", 2),
+    ("f32_decode", 256, (128, 384, 192, 320, 224, 288, 256, 256), 48, "f32", 2),
 ]
 
 
@@ -160,6 +170,7 @@ BWD_CASES = [
     ("f32_top1", 128, (32, 224, 96, 160), 150, "f32", 1),
     ("bf16_mid", 512, (96, 416, 160, 352, 224, 288, 256, 256), 1000, "bf16", 2),
     ("bf16_tails", 320, (32, 608, 288, 352), 1531, "bf16", 2),
+    ("bf16_decode", 320, (32, 608, 288, 352), 40, "bf16", 2),   # forward with saved activations: no split-K
 ]
 
 
