@@ -98,7 +98,7 @@ FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
   const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k;
   const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
   w.blockhist = c.take(nb * (L.N + 1) * 4);
-  w.near_flag = c.take((size_t)std::min<int64_t>(L.T, MODSE_SKINNY_TOKENS) * 4);
+  w.near_flag = c.take((size_t)L.T * 4);
   w.topk_idx = c.take(Tk * 4);
   w.topk_w = c.take(Tk * 4);
   w.counts = c.take(L.N * 4);

@@ -136,7 +136,7 @@ struct GateExtPtrs {
 
 // ---------------------------------------------------------------- launchers
 // route.hip
-// near_flag: [T] ints of workspace (used by the decode-sized path only)
+// near_flag: [T] ints of workspace
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
                         const RoutingPtrs& R, int32_t* blockhist, int32_t* near_flag, void* Xp, const GateExtPtrs* G,
                         hipStream_t s);

@@ -12,6 +12,7 @@ namespace {
 
 constexpr int TPB = MODSE_ROUTE_TOKENS_PER_BLOCK;  // tokens per block
 constexpr int ROUTE_THREADS = 256;
+constexpr int ROUTER_TOKEN_MAX_T = 4096;  // batches up to this size take router_token_kernel
 constexpr int TOK_PER_WAVE = TPB / (ROUTE_THREADS / 64);  // 8
 
 __device__ inline double shfl_xor_f64(double v, int mask) {
@@ -227,27 +228,33 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_kernel(const T* __res
   if (tid <= N) blockhist[(size_t)blockIdx.x * (N + 1) + tid] = s_hist[tid];
 }
 
-// Router for decode-sized batches: one block per token, the 256 threads split the d columns, so the whole
-// dot product is one or two rounds of memory latency instead of the serial passes of router_kernel.  Every
-// thread leaves its N float64 partial sums in LDS; thread e adds the 256 partials of expert e in thread
-// order (fixed, so the result does not depend on timing); thread 0 does top-k and gate.  The block
-// histograms that the permutation needs are made by route_hist_kernel from topk_idx and near_flag.
-template <typename T, int NE>
+// Router without the optional gate parts: one block per G tokens, the 256 threads split the d columns, so
+// a token row and the router matrix are read once with 16-byte loads and the whole dot product is one or
+// two rounds of memory latency.  Every thread leaves its G x N float64 partial sums in LDS; they are added
+// in two fixed-order steps (8 groups of 32 threads, then the 8 group sums), so the result does not depend
+// on timing; one thread per token then does top-k and gate.  The block histograms that the permutation
+// needs are made by route_hist_kernel from topk_idx and near_flag.
+template <typename T, int NE, int G>
 __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_token_kernel(const T* __restrict__ x,
                                                                        const T* __restrict__ Wg,
-                                                                       const float* __restrict__ bias, int d, int N,
-                                                                       int top_k, int32_t* __restrict__ topk_idx,
+                                                                       const float* __restrict__ bias, int ntok, int d,
+                                                                       int N, int top_k,
+                                                                       int32_t* __restrict__ topk_idx,
                                                                        float* __restrict__ topk_w,
                                                                        int32_t* __restrict__ near_flag) {
-  __shared__ double s_part[ROUTE_THREADS][NE + 1];  // (+1: rows start in different banks)
-  __shared__ double s_logit[NE];
-  const int tid = threadIdx.x, t = blockIdx.x;
-  double acc[NE];
+  constexpr int V = G * NE;
+  static_assert(V <= 32, "one thread per value and group in the second reduction step");
+  __shared__ double s_part[ROUTE_THREADS][V + 1];  // (+1: rows start in different banks)
+  __shared__ double s_group[8][V];
+  __shared__ double s_logit[G][NE];
+  const int tid = threadIdx.x, t0 = blockIdx.x * G;
+  double acc[V];
 #pragma unroll
-  for (int e = 0; e < NE; ++e) acc[e] = 0.0;
+  for (int v = 0; v < V; ++v) acc[v] = 0.0;
   for (int c = tid * 8; c < d; c += ROUTE_THREADS * 8) {
-    float xv[8];
-    load8(x + (size_t)t * d + c, xv);
+    float xv[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) load8(x + (size_t)min(t0 + g, ntok - 1) * d + c, xv[g]);  // (clamped rows: never written)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const T* wrow = Wg + (size_t)(c + i) * N;
@@ -258,25 +265,39 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_token_kernel(const T*
 #pragma unroll
         for (int e = 0; e < NE; ++e) wf[e] = (float)wrow[min(e, N - 1)];
       }
-      const double xd = (double)xv[i];
 #pragma unroll
-      for (int e = 0; e < NE; ++e) acc[e] = fma(xd, (double)wf[e], acc[e]);
+      for (int e = 0; e < NE; ++e) {
+        const double wd = (double)wf[e];
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc[g * NE + e] = fma((double)xv[g][i], wd, acc[g * NE + e]);
+      }
     }
   }
 #pragma unroll
-  for (int e = 0; e < NE; ++e) s_part[tid][e] = acc[e];
+  for (int v = 0; v < V; ++v) s_part[tid][v] = acc[v];
   __syncthreads();
-  if (tid < N) {
-    double sum = 0.0;
-    for (int i = 0; i < ROUTE_THREADS; ++i) sum += s_part[i][tid];
-    s_logit[tid] = sum + (bias ? (double)bias[tid] : 0.0);
+  {
+    const int v = tid & 31, grp = tid >> 5;
+    if (v < V) {
+      double sum = 0.0;
+      for (int i = 0; i < 32; ++i) sum += s_part[grp * 32 + i][v];
+      s_group[grp][v] = sum;
+    }
   }
   __syncthreads();
-  if (tid == 0) {
+  if (tid < V) {
+    double sum = 0.0;
+    for (int q = 0; q < 8; ++q) sum += s_group[q][tid];
+    const int e = tid % NE;
+    s_logit[tid / NE][e] = sum + ((bias && e < N) ? (double)bias[e] : 0.0);
+  }
+  __syncthreads();
+  if (tid < G && t0 + tid < ntok) {
+    const int t = t0 + tid;
     double m1 = -INFINITY, m2 = -INFINITY, m3 = -INFINITY;
     int i1 = 0, i2 = 0;
     for (int e = 0; e < N; ++e) {
-      const double l = s_logit[e];
+      const double l = s_logit[tid][e];
       if (l > m1) {  // strict comparisons while scanning upward: ties stay with the lower index
         m3 = m2; m2 = m1; i2 = i1; m1 = l; i1 = e;
       } else if (l > m2) {
@@ -821,12 +842,19 @@ hipError_t route_typed(const LayerDims& L, const void* xv, const void* Wgv, cons
   const T* x = static_cast<const T*>(xv);
   const T* Wg = static_cast<const T*>(Wgv);
   hipError_t e;
-  if (!G && near_flag && L.T <= MODSE_SKINNY_TOKENS && L.N <= 16) {  // decode-sized batch: one block per token
+  // Plain gate, small and medium batches: one block per token keeps the chip busy where router_kernel's
+  // 32-token blocks would leave most CUs idle (measured at d = 2048..4096: 0.04 ms instead of 0.11 ms for 64
+  // tokens; beyond a few thousand tokens router_kernel's sharing of the matrix rows wins).
+  if (!G && L.N <= 16 && L.T <= ROUTER_TOKEN_MAX_T) {
     const dim3 grid(L.T), blk(ROUTE_THREADS);
-    if (L.N <= 2) hipLaunchKernelGGL((router_token_kernel<T, 2>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
-    else if (L.N <= 4) hipLaunchKernelGGL((router_token_kernel<T, 4>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
-    else if (L.N <= 8) hipLaunchKernelGGL((router_token_kernel<T, 8>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
-    else hipLaunchKernelGGL((router_token_kernel<T, 16>), grid, blk, 0, s, x, Wg, bias, L.d, L.N, L.k, R.topk_idx, R.topk_w, near_flag);
+#define MODSE_LAUNCH_TOKEN_ROUTER(NE_)                                                                           \
+  hipLaunchKernelGGL((router_token_kernel<T, NE_, 1>), grid, blk, 0, s, x, Wg, bias, L.T, L.d, L.N, L.k, R.topk_idx, \
+                     R.topk_w, near_flag)
+    if (L.N <= 2) MODSE_LAUNCH_TOKEN_ROUTER(2);
+    else if (L.N <= 4) MODSE_LAUNCH_TOKEN_ROUTER(4);
+    else if (L.N <= 8) MODSE_LAUNCH_TOKEN_ROUTER(8);
+    else MODSE_LAUNCH_TOKEN_ROUTER(16);
+#undef MODSE_LAUNCH_TOKEN_ROUTER
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(route_hist_kernel, dim3((L.T + TPB - 1) / TPB), dim3(64), 0, s, R.topk_idx, near_flag, L.T, L.N,
                        L.k, blockhist);
