@@ -160,7 +160,7 @@ def main():
         "combine": k * T * d * b + T * d * b,
     }
     if bwd:
-        hbm_bytes["bwd_prep"] = (T * d * b + k * T * d * b) + 3 * k * T * d * b      # gather Xp; dY, O -> dO, dg
+        hbm_bytes["bwd_prep"] = 3 * k * T * d * b                                     # dY rows, O -> dO, dg
         hbm_bytes["bwd_router"] = T * d * b + k * T * d * b + T * d * b               # x, dXp rows -> dX (+ dW_gate)
     extra["hbm_stage_gbs"] = {s: round(v / (stages[s] * 1e-3) / 1e9, 1) for s, v in hbm_bytes.items() if stages[s] > 0}
     extra["hbm_stage_frac_of_peak"] = {s: round(v / PEAK_HBM_GBS, 3) for s, v in extra["hbm_stage_gbs"].items()}

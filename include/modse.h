@@ -82,8 +82,9 @@ modse_status modse_workspace_size(const modse_desc* desc, int64_t T, int need_bw
 
 /* Bytes of the DEVICE buffer `saved` that carries activations from
  * modse_layer_fwd to modse_layer_bwd (the derivatives of the SwiGLU hidden
- * activation by its two pre-activations W1 x and W3 x, the hidden activations
- * and the expert outputs, all in permuted row order).  Its layout is private. */
+ * activation by its two pre-activations W1 x and W3 x, the hidden activations,
+ * the expert outputs and the permuted token rows, all in permuted row order).
+ * Its layout is private. */
 modse_status modse_saved_size(const modse_desc* desc, int64_t T, size_t* bytes);
 
 /* Router only: logits, top-k, gate weights (Eq. 2-3) and the stable permutation

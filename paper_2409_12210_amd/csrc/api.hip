@@ -118,7 +118,7 @@ FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
 }
 
 struct SavedLayout {
-  size_t dHdA, dHdB, H, O, total;
+  size_t dHdA, dHdB, H, O, Xp, total;
 };
 
 SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
@@ -129,12 +129,13 @@ SavedLayout saved_layout(const LayerDims& L, modse_dtype dt) {
   s.dHdB = c.take(h);
   s.H = c.take(h);
   s.O = c.take((size_t)L.T * L.k * L.d * es);
+  s.Xp = c.take((size_t)L.T * L.k * L.d * es);  // permuted token rows: the weight-gradient GEMMs read them again
   s.total = c.off;
   return s;
 }
 
 struct BwdLayout {
-  size_t plan[3], Xp, dO, dA, dB, dXp, dg, dl, du, dgamma_part, dWg_partial, total;
+  size_t plan[3], dO, dA, dB, dXp, dg, dl, du, dgamma_part, dWg_partial, total;
 };
 
 BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
@@ -144,7 +145,6 @@ BwdLayout bwd_layout(const LayerDims& L, modse_dtype dt) {
   const size_t h = hidden_elems_max(L) * es;
   const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
   for (int i = 0; i < 3; ++i) w.plan[i] = c.take(sizeof(GemmPlan));
-  w.Xp = c.take(Tk * L.d * es);
   w.dO = c.take(Tk * L.d * es);
   w.dA = c.take(h);
   w.dB = c.take(h);
@@ -328,7 +328,8 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   const RoutingPtrs R = routing_from(routing_out, wsb, w);
   Stamp stamp(0, s);
 
-  void* Xp = wsb + w.Xp;
+  // with a backward pass to follow, the permuted rows go straight into the saved buffer
+  void* Xp = saved ? static_cast<char*>(saved) + saved_layout(L, dt).Xp : wsb + w.Xp;
   HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
                        reinterpret_cast<int32_t*>(wsb + w.near_flag), Xp, ext ? &G : nullptr, s));
   stamp.mark(MODSE_STAGE_ROUTE);  // routing and the row scatter share kernels; the scatter is counted here
@@ -409,10 +410,9 @@ modse_status modse_layer_bwd_ext(const modse_desc* desc, int64_t T, const void* 
                          routing->row_of,   routing->src_of, routing->near_tie_count};
   Stamp stamp(1, s);
 
-  void* Xp = wsb + w.Xp;
+  const void* Xp = sb + sl.Xp;
   void* dO = wsb + w.dO;
   float* dg = reinterpret_cast<float*>(wsb + w.dg);
-  HIP_TRY(launch_gather_rows(L, dt, x, R, Xp, s));
   HIP_TRY(launch_bwd_prep(L, dt, dY, sb + sl.O, R, dO, dg, s));
   BwdPlanArgs pa;
   std::memset(&pa, 0, sizeof(pa));

@@ -148,8 +148,6 @@ hipError_t launch_combine_split(const LayerDims& L, modse_dtype dt, const float*
                                 void* y, hipStream_t s);
 hipError_t launch_bwd_prep(const LayerDims& L, modse_dtype dt, const void* dY, const void* O, const RoutingPtrs& R,
                            void* dO, float* dg, hipStream_t s);
-hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, void* Xp,
-                              hipStream_t s);
 struct BwdRouterBufs {  // workspace of the router's backward pass
   float* dl;           // [T, N] dense gradient of the logits
   float* du;           // [T, N] gradient of x W_noise

@@ -542,19 +542,6 @@ __global__ __launch_bounds__(ROUTE_THREADS) void scatter_kernel(const T* __restr
   }
 }
 
-// Xp[r] = x[src_of[r] / k]   (one wave per permuted row)
-template <typename T>
-__global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ x, int nrows, int d, int top_k,
-                                                          const int32_t* __restrict__ src_of, T* __restrict__ Xp) {
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= nrows) return;
-  const int lane = threadIdx.x & 63;
-  const int t = src_of[r] / top_k;
-  constexpr int VEC = 16 / sizeof(T);
-  for (int c = lane * VEC; c < d; c += 64 * VEC)
-    *reinterpret_cast<f32x4*>(Xp + (size_t)r * d + c) = *reinterpret_cast<const f32x4*>(x + (size_t)t * d + c);
-}
-
 // y[t] = sum_j g[t,j] * O[row_of[t,j]]   (Eq. 1 on permuted expert outputs; one wave per token, fp32 math)
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ O, int ntok, int d, int top_k,
@@ -950,19 +937,6 @@ hipError_t launch_bwd_prep(const LayerDims& L, modse_dtype dt, const void* dY, c
     hipLaunchKernelGGL((bwd_prep_kernel<bf16_t>), dim3(nb), dim3(256), 0, s, static_cast<const bf16_t*>(dY),
                        static_cast<const bf16_t*>(O), nrows, L.d, L.k, R.src_of, R.topk_w, static_cast<bf16_t*>(dO),
                        dg);
-  return hipGetLastError();
-}
-
-hipError_t launch_gather_rows(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, void* Xp,
-                              hipStream_t s) {
-  const int nrows = L.T * L.k;
-  const int nb = (nrows + 3) / 4;
-  if (dt == MODSE_F32)
-    hipLaunchKernelGGL((gather_rows_kernel<float>), dim3(nb), dim3(256), 0, s, static_cast<const float*>(x), nrows,
-                       L.d, L.k, R.src_of, static_cast<float*>(Xp));
-  else
-    hipLaunchKernelGGL((gather_rows_kernel<bf16_t>), dim3(nb), dim3(256), 0, s, static_cast<const bf16_t*>(x), nrows,
-                       L.d, L.k, R.src_of, static_cast<bf16_t*>(Xp));
   return hipGetLastError();
 }
 
