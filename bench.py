@@ -148,6 +148,15 @@ def main():
                 "achieved": round(up_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(up_tflops / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.config, args.mode),
                 "flops_per_launch": up_flops, "avg_launch_ms": round(stages["up"], 4)}
+    if T <= 64 and not bwd:
+        # decode-sized batch: the layer streams every expert's weights once; judged against HBM bandwidth
+        wbytes = 3.0 * d * sum(cfg.d_ff) * (2 if cfg.dtype == "bf16" else 4)
+        gbs = wbytes / ((stages["up"] + stages["down"]) * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gg_bf16_kernel 64-row tiles (up-projection + split-K down-projection)",
+                    "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                    "traffic": None, "bytes_per_launch": wbytes,
+                    "avg_launch_ms": round(stages["up"] + stages["down"], 4),
+                    "whole_layer_gbs": round(wbytes / (ms_per_step * 1e-3) / 1e9, 1)}
     extra = {"fwd_grouped_gemm_tflops": round(fwd_gemm_tflops, 2),
              "fwd_grouped_gemm_frac_of_bf16_peak": round(fwd_gemm_tflops / PEAK_BF16_TFLOPS, 4),
              "down_gemm_tflops": round(down_flops / (stages["down"] * 1e-3) / 1e12, 2) if stages["down"] > 0 else 0}
