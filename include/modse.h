@@ -183,7 +183,7 @@ enum {
   MODSE_STAGE_UP = 2,       /* grouped W1/W3 GEMM + SwiGLU */
   MODSE_STAGE_DOWN = 3,     /* grouped W2 GEMM */
   MODSE_STAGE_COMBINE = 4,  /* gate-weighted unpermute */
-  MODSE_STAGE_BWD_PREP = 5, /* dO, d gate, transposes */
+  MODSE_STAGE_BWD_PREP = 5, /* dO = g dY, d gate = <dY, O>, tile plans */
   MODSE_STAGE_BWD_DGRAD = 6,/* dH (+SwiGLU backward) and dX_permuted GEMMs */
   MODSE_STAGE_BWD_WGRAD = 7,/* dW1, dW3, dW2 GEMMs */
   MODSE_STAGE_BWD_ROUTER = 8,/* dX gather, d logits, dW_gate */
