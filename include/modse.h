@@ -178,8 +178,8 @@ modse_status modse_routing_stats(const modse_desc* desc, int64_t T, const modse_
  * waits for the last recorded call and returns milliseconds per stage
  * (HOST array of MODSE_N_STAGES floats; stages not run read 0). */
 enum {
-  MODSE_STAGE_ROUTE = 0,    /* router GEMM + top-k + gate */
-  MODSE_STAGE_PERMUTE = 1,  /* histogram, scan, scatter, tile plan */
+  MODSE_STAGE_ROUTE = 0,    /* router GEMM + top-k + gate, histogram, scan, row scatter */
+  MODSE_STAGE_PERMUTE = 1,  /* device-side tile plans of the two forward GEMMs */
   MODSE_STAGE_UP = 2,       /* grouped W1/W3 GEMM + SwiGLU */
   MODSE_STAGE_DOWN = 3,     /* grouped W2 GEMM */
   MODSE_STAGE_COMBINE = 4,  /* gate-weighted unpermute */
