@@ -231,3 +231,37 @@ def test_results_are_deterministic():
     torch.cuda.synchronize()
     for a, b in zip(keep, (r.y, r.dX, r.dW_gate, r.dW1, r.dW3, r.dW2, r.routing.row_of, r.routing.src_of)):
         assert torch.equal(a, b)
+
+
+def test_layer_replays_from_a_hip_graph():
+    """The entry points allocate nothing and never synchronise, so a forward + backward pass can be captured
+    once into a HIP graph and replayed; every replay must reproduce the eager results bit for bit (with
+    eager work and synchronisations in between)."""
+    import torch
+    inp = make("graph", 256, (128, 384, 192, 320, 224, 288, 256, 256), 700, "bf16", need_dy=True)
+    r = _runner(inp, need_bwd=True)
+    r.fwd()
+    r.bwd()
+    torch.cuda.synchronize()
+    want = {n: getattr(r, n).clone() for n in ("y", "dX", "dW_gate", "dW1", "dW3", "dW2")}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        r.fwd()          # warm-up on the capture stream
+        r.bwd()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            r.fwd()
+            r.bwd()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for n in want:
+            getattr(r, n).zero_()                      # eager work between the replays
+        x2 = (r.x.float() * 2).sum()                   # (a library reduction on the default stream)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, v in want.items():
+            assert torch.equal(getattr(r, n), v), (rep, n)
+        assert torch.isfinite(x2)
