@@ -171,6 +171,9 @@ BWD_CASES = [
     ("bf16_mid", 512, (96, 416, 160, 352, 224, 288, 256, 256), 1000, "bf16", 2),
     ("bf16_tails", 320, (32, 608, 288, 352), 1531, "bf16", 2),
     ("bf16_decode", 320, (32, 608, 288, 352), 40, "bf16", 2),   # forward with saved activations: no split-K
+    # many experts: the fused weight-gradient plan is full (3 x 64 problems), several experts get no token
+    ("bf16_n64", 64, tuple(32 * (1 + e % 4) for e in range(64)), 300, "bf16", 2),
+    ("f32_n32", 96, tuple(32 * (1 + e % 3) for e in range(32)), 257, "f32", 2),
 ]
 
 
