@@ -42,7 +42,9 @@ CASES = [
     ("top1_n4", 256, (128, 384, 192, 320), 300, "bf16", 1),
     ("n16", 128, (64,) * 16, 333, "f32", 2),
     ("n3", 96, (32, 64, 96), 130, "bf16", 2),
+    ("n32", 64, (32,) * 32, 150, "f32", 2),
 ]
+LAYER_CASES = CASES[:4] + CASES[-1:]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
@@ -73,7 +75,7 @@ def test_route_ext_parity(case, noise, aux):
         assert np.abs(host(r.ext.aux_f) - np.bincount(got["topk_idx"][:T, 0], minlength=N) / T).max() < 1e-7
 
 
-@pytest.mark.parametrize("case", CASES[:4], ids=[c[0] for c in CASES[:4]])
+@pytest.mark.parametrize("case", LAYER_CASES, ids=[c[0] for c in LAYER_CASES])
 @pytest.mark.parametrize("noise,aux", [(True, True), (False, True), (True, False)])
 def test_layer_fwd_bwd_ext_parity(case, noise, aux):
     name, d, d_ff, T, dtype, k = case
