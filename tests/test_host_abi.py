@@ -124,3 +124,11 @@ def test_gate_extension_argument_checks():
                                  fake, fake, fake, 0, fake, ws_bytes=16, stream=0, raise_on_error=False) == WORKSPACE
     assert m.modse_routing_stats(*a, r, None, fake, stream=0, raise_on_error=False) == INVALID
     assert m.modse_routing_stats(*a, None, fake, fake, stream=0, raise_on_error=False) == INVALID
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode == 2
+    assert "one GPU" in p.stderr and p.stdout.strip() == ""
