@@ -64,8 +64,9 @@ __device__ inline void store4(bf16_t* p, const float v[4]) {
 
 // ---------------------------------------------------------------- grouped GEMM
 // One problem per expert:  C[M,N] (+)= A B^T (+ A2 B2^T).  How A and B lie in memory is a property of the
-// kernel instantiation (GemmLayout); lda / ldb are the row strides of the stored matrices.
-struct GemmProblem {
+// kernel instantiation (GemmLayout); lda / ldb are the row strides of the stored matrices.  The bf16 kernel
+// reads a problem with three scalar loads (64 + 32 + 8 bytes), hence the field order and the alignment.
+struct alignas(128) GemmProblem {
   const void* A;
   const void* B;
   const void* A2;  // second operand pair of a K-concatenated product (dX = dA W1 + dB W3), or null

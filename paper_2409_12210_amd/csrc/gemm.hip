@@ -8,6 +8,7 @@
 // weight-gradient GEMMs contract over tokens and read both activations as [K, M] and [K, N].
 #include "common.h"
 #include "gemm_bf16.h"
+#include "gemm_bf16_skinny.h"
 #include "gemm_tiles.h"
 
 namespace {
@@ -253,11 +254,16 @@ int num_cus() {
 template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI, int LAYOUT>
 hipError_t run_bf16(const GemmPlan* plan, int accumulate, int save_pre, int64_t max_tiles, hipStream_t s) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
-  int64_t grid = num_cus();  // the two LDS stages fill a CU: one persistent workgroup per CU
+  int64_t grid = num_cus();  // the LDS panels fill a CU: one persistent workgroup per CU
   if (max_tiles < grid) grid = max_tiles;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL((gg_bf16_kernel<BM, BN, NB, WAVES_M, WAVES_N, EPI, LAYOUT>), dim3((unsigned)grid), dim3(NT), 0, s,
-                     plan, accumulate, save_pre);
+  if constexpr (BM == 64) {  // decode-sized batches
+    hipLaunchKernelGGL((gg_bf16_skinny_kernel<BM, BN, NB, WAVES_M, WAVES_N, EPI, LAYOUT>), dim3((unsigned)grid), dim3(NT), 0,
+                       s, plan, accumulate, save_pre);
+  } else {
+    hipLaunchKernelGGL((gg_bf16_kernel<BM, BN, NB, WAVES_M, WAVES_N, EPI, LAYOUT>), dim3((unsigned)grid), dim3(NT), 0, s,
+                       plan, accumulate, save_pre);
+  }
   return hipGetLastError();
 }
 

@@ -1,68 +1,38 @@
-// bf16 grouped GEMM for gfx950: MFMA 32x32x16, fp32 accumulate, direct global->LDS loads.
+// bf16 grouped GEMM for gfx950: MFMA 32x32x16, fp32 accumulate, direct global->LDS loads, ping-pong waves
+// over a ring of five LDS panels.
 //
 // One persistent workgroup of 8 waves (WAVES_M x WAVES_N, two per SIMD) walks the tile list.  A tile is
-// BM x BN (x NB matrices B that share A: the up-projection's W1 and W3); K advances 64 elements per step.
+// 256 x 256 (up-projection: 256 x (128 of W1 + 128 of W3)); K advances 64 elements per step.
 //
-// LDS: two stages, each (BM + NB*BN) rows of 128 bytes (64 bf16 along K).  The LDS of gfx950 has 64
-// banks of 4 bytes and serves a ds_read_b128 sixteen lanes at a time; the 16-byte chunk index of a row
-// is XOR-ed with ((row >> 1) & 7), so 16 consecutive rows read at the same K offset cover all 64 banks
-// (measured: SQ_LDS_BANK_CONFLICT = 0, 4 LDS cycles per ds_read_b128).  Stages are filled by
-// global_load_lds_dwordx4: one wave instruction writes 1 KiB of consecutive LDS (8 rows); which global
-// chunk a lane fetches is chosen so that the data lands pre-swizzled.  The loads are issued from inline
-// assembly with a scalar base and a 32-bit lane offset, so every vmcnt wait is explicit here.
+// LDS: five panels of 32 KiB.  A panel holds 64 K-elements of one operand for the whole tile: 256 rows of
+// 128 bytes for a K-contiguous operand (the 16-byte chunk index of a row is XOR-ed with ((row >> 1) & 7):
+// conflict-free ds_read_b128 on the 64 banks of gfx950), or 64 K-rows of 512 bytes for an operand stored
+// [K, X] (16-byte chunk index XOR-ed with 4 * (k & 3), fragments through ds_read_b64_tr_b16).  Step g uses
+// panel 2g (A) and 2g+1 (B); panel i lives in slot i mod 5, so a panel can be refilled as soon as the step
+// two (B) or three (A) steps back has been read.
 //
-// Pipeline: the loads of stage g+1 are issued in slices between the MFMA groups of stage g (a wave that
-// blocks on a full load queue cannot feed the matrix pipe), and the K loop is rotated: the barrier that
-// opens stage g+1 and the first fragment reads of that stage sit in front of the last MFMA group of
-// stage g.  The issue cursor runs across tile boundaries, so the first stage of the next tile is in
-// flight while the epilogue of the current one stores.
+// Ping-pong: the two waves of a SIMD (wave w and w + 4) run one phase apart.  Every step has four phases
+// separated by workgroup barriers.  In a memory phase a wave only reads the MFMA fragments of one K half
+// from LDS (12 ds_read_b128); in a compute phase it issues the 16 MFMAs of that half and, in their shadow,
+// everything else: its four loads of one panel and the cursor arithmetic.  A wave issues one instruction
+// every few cycles, and the matrix pipe takes 32 cycles per MFMA, so the compute phase has issue slots to
+// spare while the memory phase has none: measured on MI355X, every scalar instruction added to the memory
+// phase lengthens the step, and four loads spread over the MFMAs of the compute phase cost nothing.
+// While a wave multiplies, its SIMD partner reads fragments, so the matrix pipe always has work.
+//
+// Every wave loads units 4w..4w+3 (1 KiB each) of every panel.  The early waves (0..3) issue the B panel
+// of the next step in their first compute phase and the A panel two steps ahead in their second one; the
+// late waves issue the A panel two steps ahead first and then the B panel two steps ahead (its slot has
+// just been retired in the phase before).  A load has between two and five phases to arrive.  The loads
+// are issued from inline assembly (the compiler does not know that they write LDS), so every vmcnt wait
+// is explicit here.
 //
 // The accumulator of v_mfma_f32_32x32x16_bf16 holds, per lane, 4 consecutive rows of the instruction's
 // first operand.  The B tile is fed as first operand, so those 4 values are consecutive columns of C.
 #pragma once
-#include "common.h"
-#include "gemm_tiles.h"
+#include "gemm_bf16_util.h"
 
 namespace modse_gemm {
-
-__device__ const uint4 g_zero_chunk[4] = {};
-  // source of K-tail chunks that lie beyond K
-
-// tells the compiler that a pointer is the same in every lane (keeps it in scalar registers)
-__device__ __forceinline__ const void* uniform_ptr(const void* p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
-}
-// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
-__device__ __forceinline__ void dma_b128(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(
-                   __builtin_amdgcn_readfirstlane(lds_base)),
-               "v"(gptr)
-               : "memory");
-}
-// same, address = wave-uniform base + per-lane unsigned 32-bit byte offset
-__device__ __forceinline__ void dma_b128_s(const void* base, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(
-                   __builtin_amdgcn_readfirstlane(lds_base)),
-               "v"(voff), "s"(uniform_ptr(base))
-               : "memory");
-}
-// 16-byte accesses through the global address space (a generic pointer would make them flat accesses)
-typedef __attribute__((address_space(1))) bf16x8 global_bf16x8;
-__device__ __forceinline__ void global_store16(bf16_t* p, bf16x8 v) { *(global_bf16x8*)(uintptr_t)p = v; }
-__device__ __forceinline__ bf16x8 global_load16(const bf16_t* p) { return *(const global_bf16x8*)(uintptr_t)p; }
-__device__ __forceinline__ uint32_t lds_address(const void* p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
-}
-
-// logistic function with the hardware reciprocal (1 ulp) instead of an IEEE division: the results are
-// rounded to bf16 anyway
-__device__ __forceinline__ float sigmoid_fast(float a) { return __builtin_amdgcn_rcpf(1.f + __expf(-a)); }
-
-#ifndef MODSE_DMA_SPREAD
-#define MODSE_DMA_SPREAD 2  // the stage loads of a step are issued in this many slices, between the MFMA groups
-#endif
 
 template <int BM, int BN, int NB, int WAVES_M, int WAVES_N>
 struct Bf16Tile {
@@ -71,189 +41,308 @@ struct Bf16Tile {
   static constexpr int NT = NWAVES * 64;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int MI = WM / 32, NI = WN / 32;
-  static constexpr int ROWS = BM + NB * BN;  // LDS rows of one stage
-  static constexpr int UA = BM / 8;          // 1 KiB load units (8 rows) of the A tile
-  static constexpr int UNITS = ROWS / 8;     // ... of the whole stage
-  static constexpr int UPW = UNITS / NWAVES; // units per wave and stage
-  static constexpr int STAGE = ROWS * 128;
-  static constexpr bool SKINNY = BM == 64;  // decode-sized M: every wave loads one A unit and UPW - 1 B units
-  static_assert(UNITS % NWAVES == 0 && (UPW % 2 == 0 || SKINNY), "load units must divide evenly among waves");
-  static_assert(MODSE_DMA_SPREAD == 2, "the stage loads go out in two slices");
+  static constexpr int PANEL = 256 * 128;  // bytes of one operand panel
+  static constexpr int NSLOT = 5;
+  static constexpr int UPW = 4;            // 1 KiB load units per wave and panel
+  static_assert(BM == 256 && NB * BN == 256 && NWAVES == 8, "panels are 256 rows, loaded by 8 waves");
   static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be a multiple of 32");
 };
 
-// Walks the K steps of this workgroup's tiles in order.
-struct StepCursor {
-  const GemmProblem* gp;  // the tile's problem (read field by field: a copy of the struct would live in scratch)
-  int tile, round, step, nsteps, nk, K;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+
+// A GemmProblem in scalar registers.  The plan is read with scalar loads issued from inline assembly: it
+// was written by an earlier kernel and nothing writes it while the GEMM runs, and a load the compiler
+// emitted as a vector load would make it wait for every panel load in flight before the value is used.
+struct ProblemRegs {
+  u32x16 lo;  // A, B, A2, B2, C, C2, C3, E1
+  u32x8 hi;   // E2, M, N, K, lda, ldb, ldc
+  u32x2 tl;   // mtiles, ntiles
+  __device__ __forceinline__ void load(const GemmProblem* p) {
+    static_assert(sizeof(GemmProblem) == 128 && alignof(GemmProblem) == 128, "scalar loads assume this layout");
+    asm volatile(
+        "s_load_dwordx16 %0, %3, 0x0\n\ts_load_dwordx8 %1, %3, 0x40\n\ts_load_dwordx2 %2, %3, 0x60\n\ts_waitcnt lgkmcnt(0)"
+        : "=&s"(lo), "=&s"(hi), "=&s"(tl)
+        : "s"(p)
+        : "memory");
+  }
+  __device__ __forceinline__ const char* ptr(int i) const {  // i-th pointer of the struct, i < 8
+    return reinterpret_cast<const char*>(((uint64_t)lo[2 * i + 1] << 32) | lo[2 * i]);
+  }
+  __device__ __forceinline__ const char* A() const { return ptr(0); }
+  __device__ __forceinline__ const char* B() const { return ptr(1); }
+  __device__ __forceinline__ const char* A2() const { return ptr(2); }
+  __device__ __forceinline__ const char* B2() const { return ptr(3); }
+  __device__ __forceinline__ void* C() const { return const_cast<char*>(ptr(4)); }
+  __device__ __forceinline__ void* C2() const { return const_cast<char*>(ptr(5)); }
+  __device__ __forceinline__ void* C3() const { return const_cast<char*>(ptr(6)); }
+  __device__ __forceinline__ const void* E1() const { return ptr(7); }
+  __device__ __forceinline__ const void* E2() const { return reinterpret_cast<const void*>(((uint64_t)hi[1] << 32) | hi[0]); }
+  __device__ __forceinline__ int M() const { return (int)hi[2]; }
+  __device__ __forceinline__ int N() const { return (int)hi[3]; }
+  __device__ __forceinline__ int K() const { return (int)hi[4]; }
+  __device__ __forceinline__ int lda() const { return (int)hi[5]; }
+  __device__ __forceinline__ int ldb() const { return (int)hi[6]; }
+  __device__ __forceinline__ int ldc() const { return (int)hi[7]; }
+  __device__ __forceinline__ int mtiles() const { return (int)tl[0]; }
+  __device__ __forceinline__ int ntiles() const { return (int)tl[1]; }
+};
+// tile_start[p] and tile_start[p + 1]
+__device__ __forceinline__ u32x2 load_tile_range(const int32_t* p) {
+  uint32_t a, b;
+  asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %2, 0x4\n\ts_waitcnt lgkmcnt(0)" : "=&s"(a), "=&s"(b) : "s"(p) : "memory");
+  return u32x2{a, b};
+}
+
+// Position in this workgroup's tile sequence.  The tiles of a workgroup come in rising order, so the
+// problem index only moves forwards.
+struct TileWalk {
+  int p, pstart, pend;  // problem of the tile and its range of the tile list
+  int mtiles, ntiles;
+  int tile, round;
   int m0, n0;
-  bool valid;
+  int valid;  // (an int: a bool that lives across loops is kept as a lane mask and tested with vector compares)
+};
+// Walks the K steps of one operand's panels, ahead of the MFMAs.
+struct LoadCursor {
+  TileWalk w;
+  int is_a;           // which operand this cursor walks
+  const char* base0;  // operand of the first pass
+  const char* base1;  // operand of the second pass of a dual-K product
+  const char* src;    // the current step's 64 K-elements of the operand (wave-uniform part of the address)
+  int rows, ld;       // rows of the stored matrix along the tile (M or N) and its row stride
+  int kbytes;         // bytes between consecutive K steps
+  int K, nk, step, nsteps;
+  int fast;           // the current step exists and is a full one (no zero fill)
+};
+// The tile being multiplied.
+struct ComputeCursor {
+  TileWalk w;
+  const char *C, *C2, *C3, *E1, *E2;
+  int M, N, ldc, nsteps;
 };
 
-// LAYOUT bit 0: A is stored [K, M] (M contiguous) instead of [M, K]; bit 1: B is stored [K, N].  Such an
-// operand keeps its memory order in LDS (64 rows of K, 512 bytes each, 32-byte chunk index XOR-ed with
-// 2 * (k & 3)) and its MFMA fragments are read with ds_read_b64_tr_b16, which hands lane i of a 16-lane
-// group the i-th column of a 4 x 16 block of 16-bit elements: 4 consecutive K for one M (or N).
+// LAYOUT bit 0: A is stored [K, M] (M contiguous) instead of [M, K]; bit 1: B is stored [K, N].
 template <int BM, int BN, int NB, int WAVES_M, int WAVES_N, int EPI, int LAYOUT = 0>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const GemmPlan* __restrict__ plan,
                                                                         int accumulate, int save_pre) {
   using Cfg = Bf16Tile<BM, BN, NB, WAVES_M, WAVES_N>;
-  constexpr int BK = Cfg::BK, MI = Cfg::MI, NI = Cfg::NI, UA = Cfg::UA, UPW = Cfg::UPW, STAGE = Cfg::STAGE;
+  constexpr int BK = Cfg::BK, MI = Cfg::MI, NI = Cfg::NI, UPW = Cfg::UPW, PANEL = Cfg::PANEL, NSLOT = Cfg::NSLOT;
   constexpr int WM = Cfg::WM, WN = Cfg::WN;
-  constexpr int SLICE0 = (UPW + 1) / 2;  // units of the first of the two load slices
-  constexpr bool SKINNY = Cfg::SKINNY;
   constexpr bool A_T = (LAYOUT & 1) != 0, B_T = (LAYOUT & 2) != 0;
-  static_assert(!SKINNY || (!A_T && !B_T && UA == Cfg::NWAVES && WAVES_M == 1), "skinny tiles: forward layouts, one A unit per wave");
-  static_assert(!(A_T && BM != 256) && !(B_T && (BN != 256 || NB != 1)), "transposed operands use 256-wide tiles");
-  static_assert(SKINNY || (UA % UPW == 0 && (BN / 8) % UPW == 0), "all load units of a wave must belong to one operand");
-  __shared__ __attribute__((aligned(1024))) char stages[2 * STAGE];
+  static_assert(!(B_T && NB != 1), "a [K, N] operand is a single matrix");
+  __shared__ __attribute__((aligned(1024))) char ring[NSLOT * PANEL];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int total = plan->tile_start[plan->n_prob];
+  const bool grp_y = wave >= Cfg::NWAVES / 2;  // the second wave of each SIMD
+  const int total = __builtin_amdgcn_readfirstlane(plan->tile_start[plan->n_prob]);
   const int first_tile = first_tile_of_block();
-  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(lds_address(stages));
-  // load unit (8 LDS rows) that this wave's i-th load of a stage fills.  Regular tiles: UPW consecutive units,
-  // all of one operand.  Skinny tiles: A unit `wave`, then UPW - 1 consecutive B units.
-  auto unit_of = [&](int i) -> int {
-    if (SKINNY) return i == 0 ? wave : UA + wave * (UPW - 1) + (i - 1);
-    return wave * UPW + i;
-  };
-  const int first_b_unit = SKINNY ? UA + wave * (UPW - 1) : wave * UPW;  // (meaningful when the wave loads B)
-  const int lrow = lane >> 3;  // row inside a load unit
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(lds_address(ring));
+  const int unit0 = wave * UPW;  // this wave loads units unit0 .. unit0 + 3 of every panel
+  const int lrow = lane >> 3;    // row inside a load unit of a K-contiguous operand
   // element offset of the chunk this lane fetches, for even and odd load units: LDS position (row, p)
   // holds logical chunk p ^ ((row >> 1) & 7), and row = 8 * unit + lrow
   const int lchunk_even = ((lane & 7) ^ (lrow >> 1)) * 8;
   const int lchunk_odd = ((lane & 7) ^ (4 | (lrow >> 1))) * 8;
-  // fragment read offsets inside a stage (bytes), without the kk-dependent swizzle term
-  const int a_frag = (wm * WM + (lane & 31)) * 128;
-  const int b_frag = BM * 128 + (wn * WN + (lane & 31)) * 128;
-  const int khalf = lane >> 5, lsw = (lane >> 1) & 7;
-  // transposed operands: this lane's row inside a load unit (2 rows of 32 chunks) and its chunk
+  // [K, X] operands: a load unit is 2 K-rows of 32 chunks; this lane's row inside the unit and its chunk
   const int t_row = lane >> 5, t_chunk = lane & 31;
-  const bool loads_a = !SKINNY && wave * UPW < UA;            // wave-uniform: which operand a regular wave loads
-  const bool loads_t = loads_a ? A_T : B_T;                   // ... and whether it is a transposed one
+  // fragment read offsets inside a panel (bytes), without the kk-dependent swizzle term
+  const int a_frag = (wm * WM + (lane & 31)) * 128;
+  const int b_frag = (wn * WN + (lane & 31)) * 128;
+  const int khalf = lane >> 5, lsw = (lane >> 1) & 7;
 
-  auto open_tile = [&](StepCursor& c) {
-    TileCoord tc;
-    c.valid = c.tile < total && decode_tile(plan, c.tile, tc);
-    if (!c.valid) return;
-    c.gp = plan->prob + tc.p;
-    c.m0 = tc.mt * BM;
-    c.n0 = tc.nt * BN;
+  // moves w to w.tile; returns true when the problem changed (then P holds the new problem)
+  auto walk_to = [&](TileWalk& w, ProblemRegs& P) -> bool {
+    w.valid = w.tile < total ? 1 : 0;
+    if (!w.valid) return false;
+    int changed = 0;
+    if (w.p < 0) {  // first tile of this walk
+      w.p = 0;
+      const u32x2 r = load_tile_range(plan->tile_start);
+      w.pstart = (int)r[0];
+      w.pend = (int)r[1];
+      changed = 1;
+    }
+    while (w.tile >= w.pend) {  // (problems without tiles are stepped over)
+      ++w.p;
+      const u32x2 r = load_tile_range(plan->tile_start + w.p);
+      w.pstart = (int)r[0];
+      w.pend = (int)r[1];
+      changed = 1;
+    }
+    if (changed) {
+      P.load(plan->prob + w.p);
+      w.mtiles = uniform_int(P.mtiles());
+      w.ntiles = uniform_int(P.ntiles());
+    }
+    const int local = w.tile - w.pstart;
+    const int per_group = GROUP_M * w.ntiles;
+    const int first = (local / per_group) * GROUP_M;
+    const int gsz = min(w.mtiles - first, GROUP_M);
+    const int rem = local % per_group;
+    w.m0 = uniform_int((first + rem % gsz) * BM);
+    w.n0 = uniform_int((rem / gsz) * BN);
+    return changed != 0;
+  };
+
+  // ---- issue side: two cursors run ahead of the MFMAs, across tile boundaries.  c0 is served in the first
+  // compute phase of a step, c1 in the second.  Early waves: c0 = B panels (one step ahead), c1 = A panels
+  // (two steps ahead); late waves: c0 = A panels (two ahead), c1 = B panels (two ahead).
+  LoadCursor c0, c1;
+  uint32_t off0[UPW], off1[UPW];  // byte offset of this lane's chunk per load unit from the cursor's src
+  // opens the tile c.w.tile (or a later one: tiles without K steps -- an expert that received no token, in
+  // a weight-gradient GEMM -- take no panel)
+  auto open_cursor = [&](LoadCursor& c, uint32_t (&off)[UPW]) {
+    for (;;) {
+      ProblemRegs P;
+      if (walk_to(c.w, P)) {
+        if (c.is_a) {
+          c.base0 = P.A();
+          c.base1 = P.A2();
+          c.rows = P.M();
+          c.ld = P.lda();
+          c.kbytes = A_T ? BK * 2 * c.ld : BK * 2;
+        } else {
+          if (NB == 2) {  // rows 0..127 of the panel come from B (W1), rows 128..255 from B2 (W3)
+            c.base0 = c.base1 = unit0 * 8 >= BN ? P.B2() : P.B();
+          } else {
+            c.base0 = P.B();
+            c.base1 = P.B2();
+          }
+          c.rows = P.N();
+          c.ld = P.ldb();
+          c.kbytes = B_T ? BK * 2 * c.ld : BK * 2;
+        }
+        c.base0 = static_cast<const char*>(uniform_ptr(c.base0));
+        c.base1 = static_cast<const char*>(uniform_ptr(c.base1));
+        c.rows = uniform_int(c.rows);
+        c.ld = uniform_int(c.ld);
+        c.kbytes = uniform_int(c.kbytes);
+        c.K = uniform_int(P.K());
+        c.nk = (c.K + BK - 1) / BK;
+        c.nsteps = (EPI == EPI_STORE_DUALK) ? 2 * c.nk : c.nk;
+      }
+      if (!c.w.valid || c.nsteps != 0) break;
+      c.w.tile = tile_of_round(first_tile, ++c.w.round);
+    }
+    c.fast = 0;
+    if (!c.w.valid) return;
     c.step = 0;
-    c.K = c.gp->K;
-    c.nk = (c.K + BK - 1) / BK;
-    c.nsteps = (EPI == EPI_STORE_DUALK) ? 2 * c.nk : c.nk;
-  };
-
-  // ---- issue side: runs one K step ahead of the MFMAs, across tile boundaries
-  StepCursor ic;
-  const char* ibase[2] = {nullptr, nullptr};  // operand this wave loads from, per pass of a dual-K product
-  const char* ibase_a = nullptr;              // skinny tiles: the A operand (unit 0 of every wave)
-  int ikstride = 1;                           // elements between consecutive K of that operand
-  uint32_t ioff[UPW];  // byte offset of this lane's chunk per load unit (K offset 0) from the operand base
-  // tiles without K steps (an expert that received no token, in a weight-gradient GEMM) take no stage
-  auto skip_empty = [&]() {
-    while (ic.valid && ic.nsteps == 0) {
-      ic.tile = tile_of_round(first_tile, ++ic.round);
-      open_tile(ic);
-    }
-  };
-  auto issue_offsets = [&]() {
-    const GemmProblem* P = ic.gp;
-    {  // operand this wave loads from (wave-uniform)
-      const int u = first_b_unit;
-      if (SKINNY) ibase_a = static_cast<const char*>(P->A);
-      if (!SKINNY && u < UA) {
-        ibase[0] = static_cast<const char*>(P->A);
-        ibase[1] = static_cast<const char*>(P->A2);
-      } else if (NB == 2) {
-        ibase[0] = ibase[1] = static_cast<const char*>((u - UA) * 8 >= BN ? P->B2 : P->B);
-      } else {
-        ibase[0] = static_cast<const char*>(P->B);
-        ibase[1] = static_cast<const char*>(P->B2);
-      }
-    }
-    const int PM = P->M, PN = P->N, lda = P->lda, ldb = P->ldb;
-    ikstride = loads_t ? (loads_a ? lda : ldb) : 1;
-    if (loads_t) {  // unit = K rows 2u, 2u+1; LDS position (k, p) holds 16-byte chunk p ^ (4 * (k & 3))
-#pragma unroll
-      for (int i = 0; i < UPW; ++i) {
-        const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
-        const int k = 2 * ul + t_row;
-        const int c16 = t_chunk ^ (4 * (k & 3));
-        const int x0 = loads_a ? ic.m0 : ic.n0, X = loads_a ? PM : PN, ld = loads_a ? lda : ldb;
-        ioff[i] = (uint32_t)(k * ld + min(x0 + c16 * 8, X - 8)) * 2u;  // columns past the end repeat the last chunk
-      }
-      return;
-    }
+    c.src = c.base0;
+    c.fast = uniform_int(BK <= c.K ? 1 : 0);
+    const bool tr = c.is_a ? A_T : B_T;
+    const int x0 = c.is_a ? c.w.m0 : c.w.n0;
 #pragma unroll
     for (int i = 0; i < UPW; ++i) {
-      const int u = unit_of(i);
-      const int lchunk = (u & 1) ? lchunk_odd : lchunk_even;  // both operand regions start at an even unit
-      if (u < UA) {
-        ioff[i] = (uint32_t)(min(ic.m0 + u * 8 + lrow, PM - 1) * lda + lchunk) * 2u;
+      const int u = unit0 + i;
+      if (tr) {  // unit = K rows 2u, 2u+1; LDS position (k, p) holds 16-byte chunk p ^ (4 * (k & 3))
+        const int k = 2 * u + t_row;
+        const int c16 = t_chunk ^ (4 * (k & 3));
+        off[i] = (uint32_t)(k * c.ld + min(x0 + c16 * 8, c.rows - 8)) * 2u;  // columns past the end repeat the last chunk
       } else {
-        const int r = ((u - UA) * 8 + lrow) % BN;
-        ioff[i] = (uint32_t)(min(ic.n0 + r, PN - 1) * ldb + lchunk) * 2u;
+        const int r = c.is_a ? u * 8 + lrow : (u * 8 + lrow) % BN;
+        off[i] = (uint32_t)(min(x0 + r, c.rows - 1) * c.ld + ((u & 1) ? lchunk_odd : lchunk_even)) * 2u;
       }
     }
   };
-  // issue load units [first, first + count) of the issue cursor's step into stage buffer `buf`
-  auto issue_slice = [&](int buf, int first, int count) {
-    if (!ic.valid) return;
-    const int pass = (EPI == EPI_STORE_DUALK && ic.step >= ic.nk) ? 1 : 0;
-    const int k0 = (ic.step - pass * ic.nk) * BK;
-    const uint32_t dst = lds_base + buf * STAGE;
-    const char* base = ibase[pass] + (size_t)k0 * ikstride * 2;
-    if (k0 + BK <= ic.K) {
+  // one load unit of the cursor's current (full) step
+  auto panel_dst = [&](int slot) -> uint32_t { return lds_base + slot * PANEL + unit0 * 1024; };  // my units of a ring slot
+  auto issue_fast = [&](const LoadCursor& c, const uint32_t (&off)[UPW], uint32_t dst, int i) {
+    dma_b128_s(c.src, off[i], dst + i * 1024);
+  };
+  // all load units of a last step that is not a full one: what lies beyond K reads zeros
+  auto issue_partial = [&](const LoadCursor& c, const uint32_t (&off)[UPW], uint32_t dst) {
+    const int kstep = (EPI == EPI_STORE_DUALK && c.step >= c.nk) ? c.step - c.nk : c.step;
+    const bool tr = c.is_a ? A_T : B_T;
 #pragma unroll
-      for (int i = first; i < first + count; ++i)
-        dma_b128_s((SKINNY && i == 0) ? ibase_a + (size_t)k0 * 2 : base, ioff[i], dst + unit_of(i) * 1024);
-    } else if (loads_t) {  // partial last step: K rows beyond K read zeros
-#pragma unroll
-      for (int i = first; i < first + count; ++i) {
-        const int ul = (wave * UPW + i) - (loads_a ? 0 : UA);
-        const char* src = base + ioff[i];
-        if (k0 + 2 * ul + t_row >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
-        dma_b128(src, dst + unit_of(i) * 1024);
-      }
-    } else {  // last step of a pass when K % 64 != 0: chunks beyond K read zeros
-#pragma unroll
-      for (int i = first; i < first + count; ++i) {
-        const char* src = ((SKINNY && i == 0) ? ibase_a + (size_t)k0 * 2 : base) + ioff[i];
-        if (k0 + ((unit_of(i) & 1) ? lchunk_odd : lchunk_even) >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
-        dma_b128(src, dst + unit_of(i) * 1024);
-      }
+    for (int i = 0; i < UPW; ++i) {
+      const char* p = c.src + off[i];
+      const int kfirst = tr ? 2 * (unit0 + i) + t_row : (((unit0 + i) & 1) ? lchunk_odd : lchunk_even);  // first K of this lane's chunk
+      if (kstep * BK + kfirst >= c.K) p = reinterpret_cast<const char*>(g_zero_chunk);
+      dma_b128(p, dst + i * 1024);
     }
   };
-  auto advance_issue = [&]() {
-    if (!ic.valid) return;
-    if (++ic.step >= ic.nsteps) {
-      ic.tile = tile_of_round(first_tile, ++ic.round);
-      open_tile(ic);
-      skip_empty();
-      if (ic.valid) issue_offsets();
+  auto advance = [&](LoadCursor& c, uint32_t (&off)[UPW]) {
+    if (!c.w.valid) return;
+    c.src += c.kbytes;
+    if (++c.step >= c.nsteps) {
+      c.w.tile = tile_of_round(first_tile, ++c.w.round);
+      open_cursor(c, off);
+      return;
+    }
+    int kstep = c.step;
+    if (EPI == EPI_STORE_DUALK && c.step >= c.nk) {
+      kstep -= c.nk;
+      if (kstep == 0) c.src = c.base1;
+    }
+    c.fast = uniform_int((kstep + 1) * BK <= c.K ? 1 : 0);
+  };
+  // whole panel of a cursor's current step, then on to the next step (prologue)
+  auto issue_panel = [&](LoadCursor& c, uint32_t (&off)[UPW], int slot) {
+    if (c.fast) {
+#pragma unroll
+      for (int i = 0; i < UPW; ++i) issue_fast(c, off, panel_dst(slot), i);
+    } else if (c.w.valid) {
+      issue_partial(c, off, panel_dst(slot));
+    }
+    advance(c, off);
+  };
+  ComputeCursor cc;
+  auto open_c = [&]() {
+    ProblemRegs P;
+    if (walk_to(cc.w, P)) {
+      cc.C = P.ptr(4);
+      cc.C2 = P.ptr(5);
+      cc.C3 = P.ptr(6);
+      cc.E1 = P.ptr(7);
+      cc.E2 = static_cast<const char*>(P.E2());
+      cc.M = P.M();
+      cc.N = P.N();
+      cc.ldc = P.ldc();
+      const int nk = (P.K() + BK - 1) / BK;
+      cc.nsteps = (EPI == EPI_STORE_DUALK) ? 2 * nk : nk;
     }
   };
 
   // ---- compute side
-  StepCursor cc;
-  cc.tile = first_tile;
-  cc.round = 0;
-  open_tile(cc);
-  if (!cc.valid) return;
-  ic = cc;
-  skip_empty();
-  if (ic.valid) issue_offsets();
-  const bool any_stage = ic.valid;
-  issue_slice(0, 0, UPW);  // stage of global step 0
-  advance_issue();
+  cc.w.p = -1;
+  cc.w.tile = first_tile;
+  cc.w.round = 0;
+  open_c();
+  if (!cc.w.valid) return;
+  c0.w = cc.w;
+  c0.w.p = -1;
+  c1.w = c0.w;
+  c0.is_a = grp_y ? 1 : 0;
+  c1.is_a = grp_y ? 0 : 1;
+  open_cursor(c0, off0);
+  open_cursor(c1, off1);
+  const int any_step = c0.w.valid;
+  // panels of step 0 and the A panel of step 1; the late waves also their share of the B panel of step 1.
+  // The last panel c1 loads here is completed (a step that is not a full one; the move to the next step) by
+  // the first memory phase, like every panel c1 loads later.
+  auto issue_fast_panel = [&](LoadCursor& c, uint32_t (&off)[UPW], int slot) {
+    if (c.fast) {
+#pragma unroll
+      for (int i = 0; i < UPW; ++i) issue_fast(c, off, panel_dst(slot), i);
+    }
+  };
+  if (!grp_y) {
+    issue_panel(c1, off1, 0);
+    issue_panel(c0, off0, 1);
+    issue_fast_panel(c1, off1, 2);
+  } else {
+    issue_panel(c0, off0, 0);
+    issue_panel(c1, off1, 1);
+    issue_panel(c0, off0, 2);
+    issue_fast_panel(c1, off1, 3);
+  }
+  int a_ahead = 0;  // the youngest UPW loads of this wave belong to an A panel that is not waited for yet
 
-  // Fragments are double-buffered in registers: set (kk & 1) feeds the MFMAs of K slice kk while the
-  // other set is being read from LDS.
+  // Fragments of one K half (two K slices of 16): set kk & 1.
   bf16x8 af[2][MI], bfr[2][NB][NI];
   // Transposed operands.  Lane l = 16 * blk + s reads, for K slice kk and half h, the 8 bytes at
   // K row kk*16 + (blk >> 1)*8 + h*4 + (s >> 2), column x = tile_x + 32*i + (blk & 1)*16 + 4*(s & 3); the
@@ -270,7 +359,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int c16 = (wn * WN + j * 32 + (blk & 1) * 16) / 8 + ((sl & 3) >> 1);
-      tr_b[j] = BM * 128 + rowbyte + ((c16 ^ (4 * kq)) << 4);
+      tr_b[j] = rowbyte + ((c16 ^ (4 * kq)) << 4);
     }
   }
   auto read_tr = [&](const char* p) -> bf16x8 {
@@ -282,47 +371,75 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
   };
-  auto load_frags = [&](const char* buf, int kk, int set) {
+  auto load_frags = [&](const char* abuf, const char* bbuf, int kk, int set) {
     const int sw = ((kk * 2 + khalf) ^ lsw) << 4;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      if (A_T) af[set][i] = read_tr(buf + tr_a[i] + kk * 16 * 512);
-      else af[set][i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + i * 32 * 128 + sw);
+      if (A_T) af[set][i] = read_tr(abuf + tr_a[i] + kk * 16 * 512);
+      else af[set][i] = *reinterpret_cast<const bf16x8*>(abuf + a_frag + i * 32 * 128 + sw);
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q)
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        if (B_T) bfr[set][q][j] = read_tr(buf + tr_b[j] + kk * 16 * 512);
-        else bfr[set][q][j] = *reinterpret_cast<const bf16x8*>(buf + b_frag + (q * BN + j * 32) * 128 + sw);
+        if (B_T) bfr[set][q][j] = read_tr(bbuf + tr_b[j] + kk * 16 * 512);
+        else bfr[set][q][j] = *reinterpret_cast<const bf16x8*>(bbuf + b_frag + (q * BN + j * 32) * 128 + sw);
       }
   };
   f32x16 acc[NB][MI][NI];
-  auto mfma_block = [&](int set) {
+  // The 16 MFMAs of one K half; in their shadow this wave's four loads of cursor c's panel (into ring slot
+  // `slot`), one after every fourth MFMA.
+  auto mfma_half = [&](LoadCursor& c, uint32_t (&off)[UPW], uint32_t dst) {
+    const int fast = c.fast;
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int q = 0; q < NB; ++q)
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[q][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][q][j], af[set][i], acc[q][i][j], 0, 0, 0);
+    for (int t = 0; t < 2 * NB * MI * NI; ++t) {
+      constexpr int PER = NB * MI * NI;
+      const int set = t / PER, r = t % PER, q = r / (MI * NI), i = (r / NI) % MI, j = r % NI;
+      acc[q][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][q][j], af[set][i], acc[q][i][j], 0, 0, 0);
+      if (t % (2 * PER / UPW) == 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (fast) issue_fast(c, off, dst, t / (2 * PER / UPW));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
   };
-  // Stage hand-over.  All my loads have landed (s_waitcnt simm16 on gfx9: vmcnt in bits [3:0] and
-  // [15:14], expcnt in [6:4], lgkmcnt in [11:8]) and my LDS reads have returned; then everybody meets.
-  // Afterwards the new stage may be read and the buffer of the old one refilled.
-  auto stage_barrier = [&]() {
-    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+  // in the memory phase that follows: a step that was not a full one is issued now, and the cursor moves on
+  auto after_issue = [&](LoadCursor& c, uint32_t (&off)[UPW], uint32_t dst) {
+    if (!c.fast && c.w.valid) issue_partial(c, off, dst);
+    advance(c, off);
+  };
+  // End of a phase: my LDS reads have returned (s_waitcnt simm16 on gfx9: vmcnt in bits [3:0] and [15:14],
+  // expcnt in [6:4], lgkmcnt in [11:8]); then everybody meets.
+  // k: which phase ends here (debug accounting only)
+  auto phase_end = [&](int k) {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
   };
+  // All my panel loads have landed except, if `ahead`, the UPW youngest (loads complete in order).
+  auto wait_panels = [&](int ahead) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (ahead) __builtin_amdgcn_s_waitcnt(0x0f70 | UPW);  // vmcnt(UPW)
+    else __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto slot_add = [&](int s, int d) { return (s + d) >= NSLOT ? s + d - NSLOT : s + d; };
 
-  int g = 0;  // global step count of this workgroup: stage buffer = g & 1
-  if (any_stage) {
-    stage_barrier();
-    load_frags(stages, 0, 0);
+  if (any_step) {
+    wait_panels(0);
+    phase_end(0);
   }
-  while (cc.valid) {
+  if (grp_y) phase_end(0);  // the second wave of each SIMD starts one phase late
+  const int d0 = grp_y ? 4 : 3, d1 = grp_y ? 0 : 4;  // ring slots of the panels c0 and c1 load, relative to the step's A panel
+  int sa = 0;  // ring slot of the current step's A panel; its B panel is in the next slot
+  while (cc.w.valid) {
 #pragma unroll
     for (int q = 0; q < NB; ++q)
 #pragma unroll
@@ -332,62 +449,73 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
 
-    // The K loop is rotated: the barrier that opens stage g+1 and the first fragment reads of that stage
-    // sit in front of the last MFMA group of stage g, so the matrix pipe has work while LDS answers.
 #pragma unroll 1
-    for (int s = 0; s < cc.nsteps; ++s, ++g) {
-      const char* buf = stages + (g & 1) * STAGE;
-      const int nbuf = (g + 1) & 1;
-      const bool next_stage = ic.valid;  // a stage g+1 exists (maybe in the next tile); uniform in the workgroup
-#pragma unroll
-      for (int kk = 0; kk < 3; ++kk) {
-        load_frags(buf, kk + 1, (kk + 1) & 1);
-        if (kk < MODSE_DMA_SPREAD) {  // the loads of stage g+1 go out in slices between the MFMA groups
-          __builtin_amdgcn_sched_barrier(0);
-          issue_slice(nbuf, kk == 0 ? 0 : SLICE0, kk == 0 ? SLICE0 : UPW - SLICE0);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        mfma_block(kk & 1);
-      }
+    for (int s = 0; s < cc.nsteps; ++s) {
+      const char* abuf = ring + sa * PANEL;
+      const char* bbuf = ring + slot_add(sa, 1) * PANEL;
+      load_frags(abuf, bbuf, 0, 0);
+      load_frags(abuf, bbuf, 1, 1);
       __builtin_amdgcn_sched_barrier(0);
-      advance_issue();
-      // (after the very last step the barrier only retires the buffer: the epilogue stages through it)
-      stage_barrier();
-      if (next_stage) load_frags(stages + nbuf * STAGE, 0, 0);
+      after_issue(c1, off1, panel_dst(slot_add(sa, grp_y ? 3 : 2)));  // (the panel c1 loaded in the step before)
+      const uint32_t dst0 = panel_dst(slot_add(sa, d0)), dst1 = panel_dst(slot_add(sa, d1));
+      if (grp_y) a_ahead = c0.w.valid;
+      phase_end(0);
+      mfma_half(c0, off0, dst0);
+      phase_end(1);
+      load_frags(abuf, bbuf, 2, 0);
+      load_frags(abuf, bbuf, 3, 1);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_block(1);
+      after_issue(c0, off0, dst0);
+      if (!grp_y) a_ahead = c1.fast;
+      // at the end of this phase of the late waves the panels of the next step must be complete
+      if (grp_y) wait_panels(a_ahead);
+      phase_end(2);
+      mfma_half(c1, off1, dst1);
+      if (!grp_y) wait_panels(a_ahead);
+      phase_end(3);
+      sa = slot_add(sa, 2);
     }
 
     // ---- epilogue.  For register group r of block (i, j) the lane holds columns n .. n+3 of row m.
-    const GemmProblem& CP = *cc.gp;
-    const int cM = CP.M, cN = CP.N, cld = CP.ldc;
-    if constexpr (EPI == EPI_STORE_F32 || SKINNY) {  // (a skinny tile's output is a few rows: stored directly)
-      const int mrow = cc.m0 + wm * WM + (lane & 31);
-      const int ncol = cc.n0 + wn * WN + 4 * khalf;
+    const int cM = cc.M, cN = cc.N, cld = cc.ldc;
+    if constexpr (EPI == EPI_STORE_F32) {
+      const int mrow = cc.w.m0 + wm * WM + (lane & 31);
+      const int ncol = cc.w.n0 + wn * WN + 4 * khalf;
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            float a[4], b[4];
+            float a[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              a[q] = acc[0][i][j][r * 4 + q];
-              b[q] = acc[NB - 1][i][j][r * 4 + q];
+            for (int q = 0; q < 4; ++q) a[q] = acc[0][i][j][r * 4 + q];
+            const int m = mrow + i * 32, n = ncol + j * 32 + r * 8;
+            if (m < cM && n < cN) {
+              float* c = reinterpret_cast<float*>(const_cast<char*>(cc.C)) + (size_t)m * cld + n;
+              if (accumulate) {
+                float old[4];
+                load4(c, old);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a[q] += old[q];
+              }
+              store4(c, a);
             }
-            epilogue4<bf16_t, EPI>(CP, mrow + i * 32, ncol + j * 32 + r * 8, a, b, accumulate, save_pre);
           }
     } else {
       // 16-bit outputs go through LDS so that global memory sees whole 128-byte lines: the wave works in
       // units of 32 rows x 64 columns (two MFMA blocks), writes a unit into a 4 KiB slot in accumulator
       // order (8 bytes per lane), reads it back row-wise (16 bytes per lane, 8 lanes per row) and stores.
-      // The two slots are the part of the retired stage buffer that only this wave's own loads refill, so
-      // no other wave is involved; LDS serves one wave's accesses in program order.
-      static_assert(NI % 2 == 0 && UPW >= 8, "staged epilogue: 64-column units, 8 KiB of stage per wave");
+      // The two slots are this wave's own load units in the two panels of the step just finished: nobody
+      // reads those panels any more, and the next loads into these units are this wave's own, issued after
+      // the epilogue.  LDS serves one wave's accesses in program order.
+      static_assert(NI % 2 == 0, "staged epilogue: 64-column units");
       constexpr int NJP = NI / 2, NU = MI * NJP;
-      char* const slot0 = stages + ((g + 1) & 1) * STAGE + first_b_unit * 1024;
-      char* const slot1 = slot0 + 4096;
+      // (the late waves have already refilled their units of the A panel's slot: they take their SIMD
+      // partner's units of the B panel's slot, which the partner stopped using a phase ago)
+      char* const slot0 = grp_y ? ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024
+                                : ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024;
+      char* const slot1 = ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024;
       const int er = lane & 31, esw = (er >> 1) & 7;
       const int rrow = lane >> 3, rchunk = lane & 7;
       auto acc_pos = [&](char* slot, int jj, int r) -> bf16x4* {  // 4 columns of accumulator group (jj, r)
@@ -397,8 +525,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         const int rr = it * 8 + rrow;
         return reinterpret_cast<bf16x8*>(slot + rr * 128 + ((rchunk ^ ((rr >> 1) & 7)) << 4));
       };
-      auto unit_m = [&](int u) { return cc.m0 + wm * WM + (u / NJP) * 32; };
-      auto unit_n = [&](int u) { return cc.n0 + wn * WN + (u % NJP) * 64; };
+      auto unit_m = [&](int u) { return cc.w.m0 + wm * WM + (u / NJP) * 32; };
+      auto unit_n = [&](int u) { return cc.w.n0 + wn * WN + (u % NJP) * 64; };
       // element offset of this lane's row-wise chunk of unit u, or -1 outside the matrix
       auto row_off = [&](int u, int it) -> long {
         const int m = unit_m(u) + it * 8 + rrow, n = unit_n(u) + rchunk * 8;
@@ -417,12 +545,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         put_block(slot, 0, c0);
         put_block(slot, 1, c1);
       };
-      auto store_unit = [&](char* slot, int u, void* C) {
+      auto store_unit = [&](char* slot, int u, const char* C) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const bf16x8 v = *row_pos(slot, it);
           const long o = row_off(u, it);
-          if (o >= 0) global_store16(static_cast<bf16_t*>(C) + o, v);
+          if (o >= 0) global_store16(reinterpret_cast<bf16_t*>(const_cast<char*>(C)) + o, v);
         }
       };
       if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
@@ -431,7 +559,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
           if (unit_m(u) >= cM) continue;
           char* slot = (u & 1) ? slot1 : slot0;
           put_unit(slot, acc[0][u / NJP][2 * (u % NJP)], acc[0][u / NJP][2 * (u % NJP) + 1]);
-          store_unit(slot, u, CP.C);
+          store_unit(slot, u, cc.C);
         }
       } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
@@ -457,11 +585,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
               *acc_pos(slot0, jj, r) = hv;
               if (save_pre) *acc_pos(slot1, jj, r) = pv;
             }
-          store_unit(slot0, u, CP.C);
+          store_unit(slot0, u, cc.C);
           if (save_pre) {
-            store_unit(slot1, u, CP.C2);
+            store_unit(slot1, u, cc.C2);
             put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
-            store_unit(slot0, u, CP.C3);
+            store_unit(slot0, u, cc.C3);
           }
         }
       } else if constexpr (EPI == EPI_SWIGLU_BWD) {
@@ -475,8 +603,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
             pa[it] = bf16x8{};
             pb[it] = bf16x8{};
             if (o >= 0) {
-              pa[it] = global_load16(static_cast<const bf16_t*>(CP.E1) + o);
-              pb[it] = global_load16(static_cast<const bf16_t*>(CP.E2) + o);
+              pa[it] = global_load16(reinterpret_cast<const bf16_t*>(cc.E1) + o);
+              pb[it] = global_load16(reinterpret_cast<const bf16_t*>(cc.E2) + o);
             }
           }
         };
@@ -509,15 +637,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
                 *acc_pos(slot0, jj, r) = da;
                 *acc_pos(slot1, jj, r) = db;
               }
-            store_unit(slot0, u, CP.C);
-            store_unit(slot1, u, CP.C2);
+            store_unit(slot0, u, cc.C);
+            store_unit(slot1, u, cc.C2);
           }
         }
       }
     }
-    cc.tile = tile_of_round(first_tile, ++cc.round);
-    open_tile(cc);
+    cc.w.tile = tile_of_round(first_tile, ++cc.w.round);
+    open_c();
   }
+  if (!grp_y) phase_end(0);  // the barrier the late waves still owe
   // drain: nothing may still be writing LDS when the workgroup's allocation is released
   __builtin_amdgcn_s_waitcnt(0x0070);
 }
