@@ -79,7 +79,9 @@ struct alignas(128) GemmProblem {
   int32_t M, N, K;
   int32_t lda, ldb, ldc;
   int32_t mtiles, ntiles;
-  int32_t pad0;
+  // tile_magic.h: reciprocals that turn the two divisions of the tile decoding into multiplications
+  uint32_t magic_group;  // by GROUP_M * ntiles (tiles in a full group of row blocks)
+  uint32_t magic_tail;   // by mtiles % GROUP_M (row blocks of the last, shorter group)
 };
 
 struct GemmPlan {

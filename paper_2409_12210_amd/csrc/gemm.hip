@@ -104,6 +104,8 @@ __device__ inline void finish_plan(GemmPlan* plan, int i, int n, int bm, int bn,
     P.mtiles = (P.M + bm - 1) / bm;
     P.ntiles = (P.N + bn - 1) / bn;
     s_tiles[q] = P.mtiles * P.ntiles;
+    P.magic_group = tile_magic((uint32_t)(GROUP_M * P.ntiles), (uint64_t)s_tiles[q]);
+    P.magic_tail = tile_magic((uint32_t)(P.mtiles % GROUP_M), (uint64_t)GROUP_M * P.ntiles);
   }
   __syncthreads();
   if (i == 0) {

@@ -49,6 +49,7 @@ struct Bf16Tile {
 };
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 
@@ -58,11 +59,11 @@ typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 struct ProblemRegs {
   u32x16 lo;  // A, B, A2, B2, C, C2, C3, E1
   u32x8 hi;   // E2, M, N, K, lda, ldb, ldc
-  u32x2 tl;   // mtiles, ntiles
+  u32x4 tl;   // mtiles, ntiles, magic_group, magic_tail
   __device__ __forceinline__ void load(const GemmProblem* p) {
     static_assert(sizeof(GemmProblem) == 128 && alignof(GemmProblem) == 128, "scalar loads assume this layout");
     asm volatile(
-        "s_load_dwordx16 %0, %3, 0x0\n\ts_load_dwordx8 %1, %3, 0x40\n\ts_load_dwordx2 %2, %3, 0x60\n\ts_waitcnt lgkmcnt(0)"
+        "s_load_dwordx16 %0, %3, 0x0\n\ts_load_dwordx8 %1, %3, 0x40\n\ts_load_dwordx4 %2, %3, 0x60\n\ts_waitcnt lgkmcnt(0)"
         : "=&s"(lo), "=&s"(hi), "=&s"(tl)
         : "s"(p)
         : "memory");
@@ -87,6 +88,8 @@ struct ProblemRegs {
   __device__ __forceinline__ int ldc() const { return (int)hi[7]; }
   __device__ __forceinline__ int mtiles() const { return (int)tl[0]; }
   __device__ __forceinline__ int ntiles() const { return (int)tl[1]; }
+  __device__ __forceinline__ uint32_t magic_group() const { return tl[2]; }
+  __device__ __forceinline__ uint32_t magic_tail() const { return tl[3]; }
 };
 // tile_start[p] and tile_start[p + 1]
 __device__ __forceinline__ u32x2 load_tile_range(const int32_t* p) {
@@ -100,6 +103,7 @@ __device__ __forceinline__ u32x2 load_tile_range(const int32_t* p) {
 struct TileWalk {
   int p, pstart, pend;  // problem of the tile and its range of the tile list
   int mtiles, ntiles;
+  uint32_t magic_group, magic_tail;
   int tile, round;
   int m0, n0;
   int valid;  // (an int: a bool that lives across loops is kept as a lane mask and tested with vector compares)
@@ -175,16 +179,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     }
     if (changed) {
       P.load(plan->prob + w.p);
-      w.mtiles = uniform_int(P.mtiles());
-      w.ntiles = uniform_int(P.ntiles());
+      w.mtiles = P.mtiles();
+      w.ntiles = P.ntiles();
+      w.magic_group = P.magic_group();
+      w.magic_tail = P.magic_tail();
     }
-    const int local = w.tile - w.pstart;
-    const int per_group = GROUP_M * w.ntiles;
-    const int first = (local / per_group) * GROUP_M;
-    const int gsz = min(w.mtiles - first, GROUP_M);
-    const int rem = local % per_group;
-    w.m0 = uniform_int((first + rem % gsz) * BM);
-    w.n0 = uniform_int((rem / gsz) * BN);
+    int mt, nt;
+    decode_local(w.tile - w.pstart, w.mtiles, w.ntiles, w.magic_group, w.magic_tail, mt, nt);
+    w.m0 = mt * BM;
+    w.n0 = nt * BN;
     return changed != 0;
   };
 
@@ -216,12 +219,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
           c.ld = P.ldb();
           c.kbytes = B_T ? BK * 2 * c.ld : BK * 2;
         }
-        c.base0 = static_cast<const char*>(uniform_ptr(c.base0));
-        c.base1 = static_cast<const char*>(uniform_ptr(c.base1));
-        c.rows = uniform_int(c.rows);
-        c.ld = uniform_int(c.ld);
-        c.kbytes = uniform_int(c.kbytes);
-        c.K = uniform_int(P.K());
+        c.base0 = static_cast<const char*>(uniform_ptr(c.base0));  // (otherwise the compiler keeps the cursor in vector registers)
+        c.K = P.K();
         c.nk = (c.K + BK - 1) / BK;
         c.nsteps = (EPI == EPI_STORE_DUALK) ? 2 * c.nk : c.nk;
       }
@@ -232,7 +231,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     if (!c.w.valid) return;
     c.step = 0;
     c.src = c.base0;
-    c.fast = uniform_int(BK <= c.K ? 1 : 0);
+    c.fast = BK <= c.K ? 1 : 0;
     const bool tr = c.is_a ? A_T : B_T;
     const int x0 = c.is_a ? c.w.m0 : c.w.n0;
 #pragma unroll
@@ -278,7 +277,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       kstep -= c.nk;
       if (kstep == 0) c.src = c.base1;
     }
-    c.fast = uniform_int((kstep + 1) * BK <= c.K ? 1 : 0);
+    c.fast = (kstep + 1) * BK <= c.K ? 1 : 0;
   };
   // whole panel of a cursor's current step, then on to the next step (prologue)
   auto issue_panel = [&](LoadCursor& c, uint32_t (&off)[UPW], int slot) {
@@ -324,12 +323,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   // panels of step 0 and the A panel of step 1; the late waves also their share of the B panel of step 1.
   // The last panel c1 loads here is completed (a step that is not a full one; the move to the next step) by
   // the first memory phase, like every panel c1 loads later.
-  auto issue_fast_panel = [&](LoadCursor& c, uint32_t (&off)[UPW], int slot) {
+  auto issue_fast_panel_dst = [&](LoadCursor& c, uint32_t (&off)[UPW], uint32_t dst) {
     if (c.fast) {
 #pragma unroll
-      for (int i = 0; i < UPW; ++i) issue_fast(c, off, panel_dst(slot), i);
+      for (int i = 0; i < UPW; ++i) issue_fast(c, off, dst, i);
     }
   };
+  auto issue_fast_panel = [&](LoadCursor& c, uint32_t (&off)[UPW], int slot) { issue_fast_panel_dst(c, off, panel_dst(slot)); };
   if (!grp_y) {
     issue_panel(c1, off1, 0);
     issue_panel(c0, off0, 1);
@@ -413,8 +413,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   };
   // End of a phase: my LDS reads have returned (s_waitcnt simm16 on gfx9: vmcnt in bits [3:0] and [15:14],
   // expcnt in [6:4], lgkmcnt in [11:8]); then everybody meets.
-  // k: which phase ends here (debug accounting only)
-  auto phase_end = [&](int k) {
+  auto phase_end = [&]() {
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
     asm volatile("" ::: "memory");
@@ -434,12 +433,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 
   if (any_step) {
     wait_panels(0);
-    phase_end(0);
+    phase_end();
   }
-  if (grp_y) phase_end(0);  // the second wave of each SIMD starts one phase late
+  if (grp_y) phase_end();  // the second wave of each SIMD starts one phase late
   const int d0 = grp_y ? 4 : 3, d1 = grp_y ? 0 : 4;  // ring slots of the panels c0 and c1 load, relative to the step's A panel
   int sa = 0;  // ring slot of the current step's A panel; its B panel is in the next slot
-  while (cc.w.valid) {
+  auto zero_acc = [&]() {
 #pragma unroll
     for (int q = 0; q < NB; ++q)
 #pragma unroll
@@ -448,7 +447,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         for (int j = 0; j < NI; ++j)
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
-
+  };
+  zero_acc();
+  while (cc.w.valid) {
 #pragma unroll 1
     for (int s = 0; s < cc.nsteps; ++s) {
       const char* abuf = ring + sa * PANEL;
@@ -459,9 +460,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       after_issue(c1, off1, panel_dst(slot_add(sa, grp_y ? 3 : 2)));  // (the panel c1 loaded in the step before)
       const uint32_t dst0 = panel_dst(slot_add(sa, d0)), dst1 = panel_dst(slot_add(sa, d1));
       if (grp_y) a_ahead = c0.w.valid;
-      phase_end(0);
+      phase_end();
       mfma_half(c0, off0, dst0);
-      phase_end(1);
+      phase_end();
       load_frags(abuf, bbuf, 2, 0);
       load_frags(abuf, bbuf, 3, 1);
       __builtin_amdgcn_sched_barrier(0);
@@ -469,18 +470,60 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       if (!grp_y) a_ahead = c1.fast;
       // at the end of this phase of the late waves the panels of the next step must be complete
       if (grp_y) wait_panels(a_ahead);
-      phase_end(2);
+      phase_end();
       mfma_half(c1, off1, dst1);
       if (!grp_y) wait_panels(a_ahead);
-      phase_end(3);
+      phase_end();
       sa = slot_add(sa, 2);
     }
 
     // ---- epilogue.  For register group r of block (i, j) the lane holds columns n .. n+3 of row m.
+    // (The lane index goes through an empty asm statement: otherwise the compiler computes the epilogue's
+    // per-lane addresses once, ahead of the tile loop, and they occupy dozens of registers in the main loop.)
+    int elane = lane;
+    asm volatile("" : "+v"(elane));
+    const int ekhalf = elane >> 5;
     const int cM = cc.M, cN = cc.N, cld = cc.ldc;
     if constexpr (EPI == EPI_STORE_F32) {
-      const int mrow = cc.w.m0 + wm * WM + (lane & 31);
-      const int ncol = cc.w.n0 + wn * WN + 4 * khalf;
+      // float32 output (weight gradients).  A tile inside the matrix that overwrites C goes through LDS, one
+      // 32 x 32 block (4 KiB) at a time: written in accumulator order (16 bytes per lane), read back row-wise,
+      // so that global memory sees whole 128-byte lines.  The slots are this wave's own load units in the
+      // two panels of the step just finished.
+      constexpr bool kStagedF32 = false;  // (switched off: the staged path does not reproduce the direct one yet)
+      const bool interior = cc.w.m0 + BM <= cM && cc.w.n0 + BN <= cN;
+      if (kStagedF32 && interior && !accumulate && cc.nsteps != 0) {
+        char* const fslot[2] = {grp_y ? ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024
+                                      : ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024,
+                                ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024};
+        const int er = elane & 31, esw = (er >> 1) & 7, rrow = elane >> 3, rchunk = elane & 7;
+        const uint32_t voff = (uint32_t)(rrow * cld + rchunk * 4) * 4u;
+        const char* const wave_c = cc.C + ((size_t)(cc.w.m0 + wm * WM) * cld + cc.w.n0 + wn * WN) * 4;
+        auto put = [&](int b) {  // block b = i * NI + j
+          f32x16& c = acc[0][b / NI][b % NI];
+          char* slot = fslot[b & 1];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            f32x4 v = {c[r * 4], c[r * 4 + 1], c[r * 4 + 2], c[r * 4 + 3]};
+            *reinterpret_cast<f32x4*>(slot + er * 128 + (((2 * r + ekhalf) ^ esw) << 4)) = v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) c[r * 4 + q] = 0.f;
+          }
+        };
+        put(0);
+#pragma unroll
+        for (int b = 0; b < MI * NI; ++b) {
+          if (b + 1 < MI * NI) put(b + 1);
+          char* slot = fslot[b & 1];
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {
+            const int rr = it * 8 + rrow;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(slot + rr * 128 + ((rchunk ^ ((rr >> 1) & 7)) << 4));
+            global_store16_s(wave_c + ((size_t)((b / NI) * 32 + it * 8) * cld + (b % NI) * 32) * 4, voff, v);
+          }
+        }
+      } else {
+      const int mrow = cc.w.m0 + wm * WM + (elane & 31);
+      const int ncol = cc.w.n0 + wn * WN + 4 * ekhalf;
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -502,6 +545,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
               store4(c, a);
             }
           }
+      }
     } else {
       // 16-bit outputs go through LDS so that global memory sees whole 128-byte lines: the wave works in
       // units of 32 rows x 64 columns (two MFMA blocks), writes a unit into a 4 KiB slot in accumulator
@@ -516,10 +560,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       char* const slot0 = grp_y ? ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024
                                 : ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024;
       char* const slot1 = ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024;
-      const int er = lane & 31, esw = (er >> 1) & 7;
-      const int rrow = lane >> 3, rchunk = lane & 7;
+      const int er = elane & 31, esw = (er >> 1) & 7;
+      const int rrow = elane >> 3, rchunk = elane & 7;
       auto acc_pos = [&](char* slot, int jj, int r) -> bf16x4* {  // 4 columns of accumulator group (jj, r)
-        return reinterpret_cast<bf16x4*>(slot + er * 128 + (((jj * 4 + r) ^ esw) << 4) + khalf * 8);
+        return reinterpret_cast<bf16x4*>(slot + er * 128 + (((jj * 4 + r) ^ esw) << 4) + ekhalf * 8);
       };
       auto row_pos = [&](char* slot, int it) -> bf16x8* {  // chunk rchunk of row 8 * it + rrow
         const int rr = it * 8 + rrow;
@@ -532,16 +576,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
         const int m = unit_m(u) + it * 8 + rrow, n = unit_n(u) + rchunk * 8;
         return (m < cM && n < cN) ? (long)m * cld + n : -1;
       };
-      auto put_block = [&](char* slot, int jj, const f32x16& c) {  // one 32 x 32 block of the unit
+      // one 32 x 32 block of the unit; the accumulator block is cleared for the next tile on the way
+      auto put_block = [&](char* slot, int jj, f32x16& c) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           bf16x4 v;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) v[q] = (bf16_t)c[r * 4 + q];
+          for (int q = 0; q < 4; ++q) {
+            v[q] = (bf16_t)c[r * 4 + q];
+            c[r * 4 + q] = 0.f;
+          }
           *acc_pos(slot, jj, r) = v;
         }
       };
-      auto put_unit = [&](char* slot, const f32x16& c0, const f32x16& c1) {
+      auto put_unit = [&](char* slot, f32x16& c0, f32x16& c1) {
         put_block(slot, 0, c0);
         put_block(slot, 1, c1);
       };
@@ -553,6 +601,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
           if (o >= 0) global_store16(reinterpret_cast<bf16_t*>(const_cast<char*>(C)) + o, v);
         }
       };
+      // A tile that lies inside the matrix needs no masks: its stores take the tile's address from scalar
+      // registers and one per-lane offset that is the same for every store of the tile.
+      const bool interior = cc.w.m0 + BM <= cM && cc.w.n0 + BN <= cN;
+      const uint32_t voff = (uint32_t)(rrow * cld + rchunk * 8) * 2u;
+      const char* const wave_c = cc.C + ((size_t)(cc.w.m0 + wm * WM) * cld + cc.w.n0 + wn * WN) * 2;
       if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
@@ -593,60 +646,88 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
           }
         }
       } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-        // the saved terms p = dh/da and q = dh/db of the unit come in row-wise (whole lines), one unit ahead
-        // of the arithmetic; da = dh p and db = dh q replace them in the slots at the positions the lane read
-        bf16x8 pa[4], pb[4];
-        auto fetch = [&](int u) {
+        {
+          // dh goes through LDS as float32, one unit (32 rows x 64 columns, 8 KiB = both slots) at a time:
+          // written in accumulator order, read back row-wise.  The saved terms p = dh/da and q = dh/db come
+          // from global memory row-wise (whole lines) into registers, one unit ahead: each pair of registers
+          // is reloaded for the next unit as soon as it has been multiplied.  da = dh p and db = dh q leave
+          // row-wise as well.  The loads are never masked (a load that is skipped would break the counting of
+          // the waits, and a conditionally assigned register may be copied before its load has returned):
+          // rows and chunks beyond the matrix read the last row / chunk instead; the stores are masked.
+          const size_t tile_off = ((size_t)cc.w.m0 * cld + cc.w.n0) * 2;
+          const char* const tile_c = cc.C + tile_off;
+          const char* const tile_c2 = cc.C2 + tile_off;
+          const char* const tile_e1 = cc.E1 + tile_off;
+          const char* const tile_e2 = cc.E2 + tile_off;
+          const int mrel = wm * WM + rrow, nrel = wn * WN + rchunk * 8;   // this lane's position in the tile (unit 0, row group 0)
+          const int mmax = cM - 1 - cc.w.m0, nmax = cN - 8 - cc.w.n0;    // last row / chunk of the matrix, tile-relative
+          auto lane_off = [&](int u, int it) -> uint32_t {
+            const int m = min(mrel + (u / NJP) * 32 + it * 8, mmax), n = min(nrel + (u % NJP) * 64, nmax);
+            return (uint32_t)(m * cld + n) * 2u;
+          };
+          auto inside = [&](int u, int it) { return mrel + (u / NJP) * 32 + it * 8 <= mmax && nrel + (u % NJP) * 64 <= nmax; };
+          auto frow = [&](int rr) -> char* { return (rr < 16 ? slot0 : slot1) + (rr & 15) * 256; };
+          bf16x8 pa[4], pb[4];
 #pragma unroll
           for (int it = 0; it < 4; ++it) {
-            const long o = row_off(u, it);
-            pa[it] = bf16x8{};
-            pb[it] = bf16x8{};
-            if (o >= 0) {
-              pa[it] = global_load16(reinterpret_cast<const bf16_t*>(cc.E1) + o);
-              pb[it] = global_load16(reinterpret_cast<const bf16_t*>(cc.E2) + o);
-            }
+            const uint32_t o = lane_off(0, it);
+            pa[it] = global_load16_s(tile_e1, o);
+            pb[it] = global_load16_s(tile_e2, o);
           }
-        };
-        fetch(0);
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-          const int i = u / NJP, j0 = 2 * (u % NJP);
-          const bool active = unit_m(u) < cM;
-          if (active) {
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-              *row_pos(slot0, it) = pa[it];
-              *row_pos(slot1, it) = pb[it];
-            }
-          }
-          if (u + 1 < NU) fetch(u + 1);
-          if (active) {
+          for (int u = 0; u < NU; ++u) {
+            const int i = u / NJP, j0 = 2 * (u % NJP);
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
-                const bf16x4 av = *acc_pos(slot0, jj, r), bv = *acc_pos(slot1, jj, r);
-                bf16x4 da, db;
+                f32x16& c = acc[0][i][j0 + jj];
+                const f32x4 v = {c[r * 4], c[r * 4 + 1], c[r * 4 + 2], c[r * 4 + 3]};
+                *reinterpret_cast<f32x4*>(frow(er) + (((jj * 8 + 2 * r + ekhalf) ^ (er & 15)) << 4)) = v;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                  const float dh = acc[0][i][j0 + jj][r * 4 + q];
-                  da[q] = (bf16_t)(dh * (float)av[q]);
-                  db[q] = (bf16_t)(dh * (float)bv[q]);
-                }
-                *acc_pos(slot0, jj, r) = da;
-                *acc_pos(slot1, jj, r) = db;
+                for (int q = 0; q < 4; ++q) c[r * 4 + q] = 0.f;
               }
-            store_unit(slot0, u, cc.C);
-            store_unit(slot1, u, cc.C2);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+              __builtin_amdgcn_sched_barrier(0);  // (keeps the compiler from hoisting the address arithmetic of all rows: registers are short here)
+              f32x4 dhr[2];
+              {
+                const int rr = it * 8 + rrow;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) dhr[h] = *reinterpret_cast<const f32x4*>(frow(rr) + (((2 * rchunk + h) ^ (rr & 15)) << 4));
+              }
+              // loads issued after this pair: the rest of this unit's, and the next unit's reloaded so far
+              if (u + 1 < NU || it == 0) wait_loaded<6>(pa[it], pb[it]);
+              else if (it == 1) wait_loaded<4>(pa[it], pb[it]);
+              else if (it == 2) wait_loaded<2>(pa[it], pb[it]);
+              else wait_loaded<0>(pa[it], pb[it]);
+              bf16x8 da, db;
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {
+                const float dh = dhr[q / 4][q % 4];
+                da[q] = (bf16_t)(dh * (float)pa[it][q]);
+                db[q] = (bf16_t)(dh * (float)pb[it][q]);
+              }
+              if (u + 1 < NU) {
+                const uint32_t o = lane_off(u + 1, it);
+                pa[it] = global_load16_s(tile_e1, o);
+                pb[it] = global_load16_s(tile_e2, o);
+              }
+              if (inside(u, it)) {
+                const uint32_t o = lane_off(u, it);
+                global_store16_s(tile_c, o, da);
+                global_store16_s(tile_c2, o, db);
+              }
+            }
           }
         }
       }
     }
+    zero_acc();
     cc.w.tile = tile_of_round(first_tile, ++cc.w.round);
     open_c();
   }
-  if (!grp_y) phase_end(0);  // the barrier the late waves still owe
+  if (!grp_y) phase_end();  // the barrier the late waves still owe
   // drain: nothing may still be writing LDS when the workgroup's allocation is released
   __builtin_amdgcn_s_waitcnt(0x0070);
 }

@@ -33,6 +33,26 @@ __device__ __forceinline__ void dma_b128_s(const void* base, uint32_t voff, uint
 typedef __attribute__((address_space(1))) bf16x8 global_bf16x8;
 __device__ __forceinline__ void global_store16(bf16_t* p, bf16x8 v) { *(global_bf16x8*)(uintptr_t)p = v; }
 __device__ __forceinline__ bf16x8 global_load16(const bf16_t* p) { return *(const global_bf16x8*)(uintptr_t)p; }
+// 16 bytes per lane to / from wave-uniform base + per-lane unsigned 32-bit byte offset.  The load is issued
+// from assembly so that its wait can be written by hand: the compiler waits for every outstanding memory
+// operation as soon as loads and stores are mixed.  wait_loaded makes the values usable once at most
+// `younger` vector-memory loads issued after them are still in flight (loads complete in order).
+__device__ __forceinline__ void global_store16_s(const void* base, uint32_t voff, bf16x8 v) {
+  asm volatile("global_store_dwordx4 %0, %1, %2" ::"v"(voff), "v"(v), "s"(base) : "memory");
+}
+__device__ __forceinline__ void global_store16_s(const void* base, uint32_t voff, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, %2" ::"v"(voff), "v"(v), "s"(base) : "memory");
+}
+__device__ __forceinline__ bf16x8 global_load16_s(const void* base, uint32_t voff) {
+  bf16x8 v;
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(voff), "s"(base) : "memory");
+  return v;
+}
+template <int YOUNGER>
+__device__ __forceinline__ void wait_loaded(bf16x8& a, bf16x8& b) {
+  static_assert(YOUNGER >= 0 && YOUNGER < 16, "vmcnt field");
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(YOUNGER) : "memory");
+}
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }

@@ -4,12 +4,44 @@
 
 namespace modse_gemm {
 
+#ifndef MAGIC_ONLY
+#define MAGIC_ONLY 0
+#endif
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;  // tiles of GROUP_M consecutive row blocks are walked column-first (L2 reuse)
 
 struct TileCoord {
   int p, mt, nt;
 };
+
+// Division by a positive divisor d through one multiplication: floor(n / d) == mulhi(n, ceil(2^32 / d))
+// whenever n * d < 2^32.  tile_magic returns 0 when the caller's largest n does not satisfy that (the
+// decoding then divides).
+__host__ __device__ inline uint32_t tile_magic(uint32_t d, uint64_t n_max) {
+  if (d <= 1 || n_max * d >= (1ull << 32)) return 0;
+  return (uint32_t)(((1ull << 32) + d - 1) / d);
+}
+__device__ inline uint32_t magic_div(uint32_t n, uint32_t d, uint32_t magic) {
+  return MAGIC_ONLY ? __umulhi(n, magic) : (magic ? __umulhi(n, magic) : n / d);
+}
+
+// Tile `local` of a problem with mtiles x ntiles tiles: tiles are walked in groups of GROUP_M row blocks,
+// column-first inside a group.
+__device__ inline void decode_local(int local, int mtiles, int ntiles, uint32_t magic_group, uint32_t magic_tail, int& mt,
+                                    int& nt) {
+  const int per_group = GROUP_M * ntiles;
+  const int g = (int)magic_div((uint32_t)local, (uint32_t)per_group, magic_group);
+  const int first = g * GROUP_M;
+  const int rem = local - g * per_group;
+  const int gsz = min(mtiles - first, GROUP_M);
+  if (gsz == GROUP_M) {
+    nt = rem / GROUP_M;
+    mt = first + rem % GROUP_M;
+  } else {
+    nt = (int)magic_div((uint32_t)rem, (uint32_t)gsz, magic_tail);
+    mt = first + rem - nt * gsz;
+  }
+}
 
 __device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, TileCoord& tc) {
   const int np = plan->n_prob;
@@ -21,15 +53,9 @@ __device__ inline bool decode_tile(const GemmPlan* __restrict__ plan, int tile, 
     else hi = mid;
   }
   const int p = lo;
-  const int local = tile - plan->tile_start[p];
-  const int mtiles = plan->prob[p].mtiles, ntiles = plan->prob[p].ntiles;
-  const int per_group = GROUP_M * ntiles;
-  const int first = (local / per_group) * GROUP_M;
-  const int gsz = min(mtiles - first, GROUP_M);
-  const int rem = local % per_group;
+  const GemmProblem& P = plan->prob[p];
   tc.p = p;
-  tc.mt = first + rem % gsz;
-  tc.nt = rem / gsz;
+  decode_local(tile - plan->tile_start[p], P.mtiles, P.ntiles, P.magic_group, P.magic_tail, tc.mt, tc.nt);
   return true;
 }
 
