@@ -94,6 +94,20 @@ modse_status modse_route(const modse_desc* desc, int64_t T, const void* x, const
                          const float* logit_bias, const modse_routing* out, void* ws, size_t ws_bytes,
                          void* hip_stream);
 
+/* modse_route for callers that cannot allocate or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The router's scratch (per-block histograms, near-tie flags) is a device
+ * array inside the library, MODSE_ROUTE_STATIC_SCRATCH_BYTES per GPU, held
+ * until the process ends; the call allocates and frees nothing.  Same
+ * arguments, results and checks as modse_route otherwise.  The array serves
+ * any supported layer up to 65536 tokens (the need is about
+ * T * (4 + (n_experts + 1) / 8) bytes); a larger T that does not fit returns
+ * MODSE_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams) race. */
+#define MODSE_ROUTE_STATIC_SCRATCH_BYTES (1u << 20)
+modse_status modse_route_static(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                                const float* logit_bias, const modse_routing* out, void* hip_stream);
+
 /* Forward pass of the layer (Eq. 1 with diverse-size experts, Sec. 3.1):
  * route, permute, grouped up-projection with SwiGLU, grouped down-projection,
  * gate-weighted combine.  y [T,d] DEVICE out.  routing_out may be NULL unless

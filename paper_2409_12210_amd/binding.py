@@ -58,6 +58,7 @@ def load_library():
     lib.modse_workspace_size.argtypes = [dp, i64, C.c_int, C.POINTER(sz)]
     lib.modse_saved_size.argtypes = [dp, i64, C.POINTER(sz)]
     lib.modse_route.argtypes = [dp, i64, vp, vp, vp, rp, vp, sz, vp]
+    lib.modse_route_static.argtypes = [dp, i64, vp, vp, vp, rp, vp]
     lib.modse_layer_fwd.argtypes = [dp, i64, vp, vp, vp, vp, vp, vp, vp, rp, vp, vp, sz, vp]
     lib.modse_layer_bwd.argtypes = [dp, i64, vp, vp, vp, vp, vp, rp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
     ep = C.POINTER(_GateExt)
@@ -70,6 +71,7 @@ def load_library():
     lib.modse_stage_times.argtypes = [C.POINTER(C.c_float)]
     for name in ("modse_workspace_size", "modse_saved_size", "modse_route", "modse_layer_fwd", "modse_layer_bwd",
                  "modse_route_ext", "modse_layer_fwd_ext", "modse_layer_bwd_ext", "modse_routing_stats",
+                 "modse_route_static",
                  "modse_stage_timing_enable", "modse_stage_times"):
         getattr(lib, name).restype = C.c_int
     _LIB = lib
@@ -188,6 +190,15 @@ def modse_route(d_model, d_ff, top_k, dtype, T, x, W_gate, logit_bias, routing: 
     code = load_library().modse_route(C.byref(d), int(T), _ptr(x), _ptr(W_gate), _ptr(logit_bias),
                                       C.byref(r) if r is not None else None, _ptr(ws), nbytes, _stream(stream))
     return _check(code, "modse_route", raise_on_error)
+
+
+def modse_route_static(d_model, d_ff, top_k, dtype, T, x, W_gate, logit_bias, routing: Routing, stream=None,
+                       raise_on_error=True) -> int:
+    d = _desc(d_model, d_ff, top_k, dtype)
+    r = routing._c() if routing is not None else None
+    code = load_library().modse_route_static(C.byref(d), int(T), _ptr(x), _ptr(W_gate), _ptr(logit_bias),
+                                             C.byref(r) if r is not None else None, _stream(stream))
+    return _check(code, "modse_route_static", raise_on_error)
 
 
 def modse_layer_fwd(d_model, d_ff, top_k, dtype, T, x, W_gate, logit_bias, W1, W3, W2, y,

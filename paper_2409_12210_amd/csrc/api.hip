@@ -290,6 +290,57 @@ modse_status modse_route_ext(const modse_desc* desc, int64_t T, const void* x, c
   return MODSE_OK;
 }
 
+// ---------------------------------------------------------------- modse_route without a workspace
+// For callers that cannot hand over a workspace they allocated (HIP graph capture, serving loops that must
+// not allocate): the router's scratch -- per-block histograms and near-tie flags -- lives in a device array
+// of this library.  Every GPU holds its own copy at its own address; the name below is only the host-side
+// handle of the symbol, the address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char g_route_scratch[MODSE_ROUTE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_route_scratch_ptr[kMaxDevices] = {};
+
+// the part of the forward workspace that modse_route uses, laid out as fwd_layout does
+struct RouteScratch {
+  size_t blockhist, near_flag, total;
+};
+RouteScratch route_scratch_layout(const LayerDims& L) {
+  RouteScratch r;
+  Carver c;
+  const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
+  r.blockhist = c.take(nb * (L.N + 1) * 4);
+  r.near_flag = c.take((size_t)L.T * 4);
+  r.total = c.off;
+  return r;
+}
+}  // namespace
+
+modse_status modse_route_static(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
+                                const float* logit_bias, const modse_routing* out, void* hip_stream) {
+  const modse_status st = check_desc(desc, T);
+  if (st != MODSE_OK) return st;
+  if (T == 0) return MODSE_OK;
+  if (!x || !W_gate || !routing_complete(out)) return MODSE_ERR_INVALID_ARG;
+  const LayerDims L = make_dims(desc, T);
+  const RouteScratch w = route_scratch_layout(L);
+  if (w.total > MODSE_ROUTE_STATIC_SCRATCH_BYTES) return MODSE_ERR_WORKSPACE;  // more tokens than the array serves
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MODSE_ERR_HIP;
+  if (!g_route_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_route_scratch)) != hipSuccess || !p) return MODSE_ERR_HIP;
+    g_route_scratch_ptr[dev] = p;
+  }
+  char* scratch = static_cast<char*>(g_route_scratch_ptr[dev]);
+  const RoutingPtrs R = {out->topk_idx, out->topk_w, out->counts, out->offsets, out->row_of, out->src_of, out->near_tie_count};
+  // every word of the scratch that a kernel reads has been written by an earlier kernel of this call
+  HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(scratch + w.blockhist),
+                       reinterpret_cast<int32_t*>(scratch + w.near_flag), nullptr, nullptr,
+                       static_cast<hipStream_t>(hip_stream)));
+  return MODSE_OK;
+}
+
 modse_status modse_routing_stats(const modse_desc* desc, int64_t T, const modse_routing* routing,
                                  int32_t* slot_counts, float* summary, void* hip_stream) {
   const modse_status st = check_desc(desc, T);

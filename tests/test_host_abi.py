@@ -91,6 +91,18 @@ def test_calls_reject_null_pointers_and_small_workspace_before_any_launch():
         m.modse_route(*a, None, None, None, None, None, stream=0)
 
 
+def test_route_static_checks_arguments_and_its_fixed_scratch_size_before_any_launch():
+    fake = 0x1000
+    r = m.Routing(fake, fake, fake, fake, fake, fake, fake)
+    a = (C0["d_model"], C0["d_ff"], C0["top_k"], C0["dtype"])
+    assert m.modse_route_static(*a, 16, None, None, None, None, stream=0, raise_on_error=False) == INVALID
+    assert m.modse_route_static(*a, 0, None, None, None, None, stream=0, raise_on_error=False) == OK
+    assert m.modse_route_static(*a, -1, fake, fake, None, r, stream=0, raise_on_error=False) == INVALID
+    # 2**18 tokens need about 3 MiB of histograms and flags at 64 experts: more than the library's array
+    assert m.modse_route_static(64, [32] * 64, 2, "f32", 1 << 18, fake, fake, None, r, stream=0,
+                                raise_on_error=False) == WORKSPACE
+
+
 def test_zero_tokens_is_a_noop():
     a = (C0["d_model"], C0["d_ff"], C0["top_k"], C0["dtype"], 0)
     assert m.modse_layer_fwd(*a, None, None, None, None, None, None, None, None, None, None, ws_bytes=0, stream=0,
