@@ -132,17 +132,14 @@ def router_logits(x, W_gate, logit_bias=None, noise: Optional["Noise"] = None):
 
 
 def top_k_indices(logits, k):
-    """Indices of the k largest logits per row, largest first; ties -> lower
-    index (np.argmax returns the first maximum)."""
-    work = np.array(logits, dtype=F64, copy=True)
-    T = work.shape[0]
-    idx = np.empty((T, k), dtype=np.int32)
-    rows = np.arange(T)
-    for j in range(k):
-        i = np.argmax(work, axis=1)
-        idx[:, j] = i
-        work[rows, i] = -np.inf
-    return idx
+    """Positions of the k largest logits per row, largest first (KeepTopK, Eq. 3,
+    keeps k distinct positions of the vector); ties -> lower index.  Written
+    as the definition: a stable sort by descending value, first k positions.
+    Logits of -inf (experts masked out by a bias) sort last like any other
+    value, so the picks stay distinct even when fewer than k logits are finite."""
+    work = np.asarray(logits, dtype=F64)
+    order = np.argsort(-work, axis=1, kind="stable")
+    return np.ascontiguousarray(order[:, :k]).astype(np.int32)
 
 
 def gate_dense(logits, idx):

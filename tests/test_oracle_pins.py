@@ -133,6 +133,33 @@ def test_topk_brute_force_with_ties():
     assert list(orc.top_k_indices(logits, 2)[2]) == [0, 1]
 
 
+def test_topk_picks_are_distinct_when_experts_are_masked_out():
+    # Eq. 3 keeps k distinct positions.  With all but one logit at -inf (experts masked by a bias) the second
+    # pick is the lowest other index and its gate weight is exactly 0.  Checked against hand values and against
+    # a loop that removes each winner from the candidate set.
+    ninf = -np.inf
+    logits = np.array([[0.3, ninf, ninf, ninf, ninf, ninf, ninf, ninf],
+                       [ninf, ninf, ninf, ninf, ninf, 1.5, ninf, ninf],
+                       [ninf] * 8,
+                       [ninf, ninf, 2.0, ninf, 2.0, ninf, ninf, ninf],
+                       [ninf, -1.0, ninf, ninf, ninf, ninf, ninf, 7.0]])
+    want = [[0, 1], [5, 0], [0, 1], [2, 4], [7, 1]]
+    idx = orc.top_k_indices(logits, 2)
+    assert idx.tolist() == want
+    for t in range(logits.shape[0]):
+        left = list(range(8))
+        for j in range(3):
+            best = left[0]
+            for i in left[1:]:
+                if logits[t, i] > logits[t, best]:
+                    best = i
+            assert orc.top_k_indices(logits, 3)[t, j] == best
+            left.remove(best)
+    w = orc.gate_weights(logits[[0, 1, 4]], idx[[0, 1, 4]])
+    assert w[:2].tolist() == [[1.0, 0.0], [1.0, 0.0]]
+    assert abs(w[2, 0] - 1 / (1 + np.exp(-8.0))) < 1e-15 and abs(w[2].sum() - 1) < 1e-15
+
+
 def test_near_tie_mask():
     logits = np.array([[1.0, 0.5, 0.5 - 5e-7, -3.0],     # 2nd/3rd gap below tol
                        [1.0, 1.0 - 5e-7, 0.0, -3.0],     # 1st/2nd gap below tol
