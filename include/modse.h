@@ -76,9 +76,17 @@ typedef struct {
                               logits among their top_k+1 largest */
 } modse_routing;
 
-/* Bytes of DEVICE workspace `ws` that modse_route / modse_layer_fwd
- * (need_bwd = 0) or modse_layer_bwd (need_bwd = 1) require for T tokens. */
-modse_status modse_workspace_size(const modse_desc* desc, int64_t T, int need_bwd, size_t* bytes);
+/* Bytes of DEVICE workspace `ws` that a call requires for T tokens.  `which`:
+ * MODSE_WS_FWD for modse_route and for modse_layer_fwd without `saved`,
+ * MODSE_WS_BWD for modse_layer_bwd, MODSE_WS_FWD_SAVED for modse_layer_fwd
+ * with `saved` (the permuted rows, hidden activations and expert outputs then
+ * live in `saved`, and the workspace holds routing scratch and tile plans
+ * only; a MODSE_WS_FWD workspace also serves that call).  Any other value:
+ * MODSE_ERR_INVALID_ARG. */
+#define MODSE_WS_FWD 0
+#define MODSE_WS_BWD 1
+#define MODSE_WS_FWD_SAVED 2
+modse_status modse_workspace_size(const modse_desc* desc, int64_t T, int which, size_t* bytes);
 
 /* Bytes of the DEVICE buffer `saved` that carries activations from
  * modse_layer_fwd to modse_layer_bwd (the derivatives of the SwiGLU hidden
@@ -99,10 +107,12 @@ modse_status modse_route(const modse_desc* desc, int64_t T, const void* x, const
  * The router's scratch (per-block histograms, near-tie flags) is a device
  * array inside the library, MODSE_ROUTE_STATIC_SCRATCH_BYTES per GPU, held
  * until the process ends; the call allocates and frees nothing.  Same
- * arguments, results and checks as modse_route otherwise.  The array serves
- * any supported layer up to 65536 tokens (the need is about
- * T * (4 + (n_experts + 1) / 8) bytes); a larger T that does not fit returns
- * MODSE_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the array: calls that
+ * arguments, results and checks as modse_route otherwise.  The need is about
+ * T * (4 + (n_experts + 1) / 8) bytes, so the array serves 65536 tokens at
+ * any expert count that is a power of two (other counts also keep a padded
+ * copy of W_gate there, 2 * d_model * 64 elements at most); a call whose
+ * scratch does not fit returns MODSE_ERR_WORKSPACE before anything is
+ * launched.  All calls on one GPU share the array: calls that
  * overlap in time on one GPU (different streams) race. */
 #define MODSE_ROUTE_STATIC_SCRATCH_BYTES (1u << 20)
 modse_status modse_route_static(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
@@ -192,8 +202,8 @@ modse_status modse_routing_stats(const modse_desc* desc, int64_t T, const modse_
  * waits for the last recorded call and returns milliseconds per stage
  * (HOST array of MODSE_N_STAGES floats; stages not run read 0). */
 enum {
-  MODSE_STAGE_ROUTE = 0,    /* router GEMM + top-k + gate, histogram, scan, row scatter */
-  MODSE_STAGE_PERMUTE = 1,  /* device-side tile plans of the two forward GEMMs */
+  MODSE_STAGE_ROUTE = 0,    /* router GEMM + top-k + gate (+ auxiliary loss) */
+  MODSE_STAGE_PERMUTE = 1,  /* histogram, scan over blocks, stable row scatter */
   MODSE_STAGE_UP = 2,       /* grouped W1/W3 GEMM + SwiGLU */
   MODSE_STAGE_DOWN = 3,     /* grouped W2 GEMM */
   MODSE_STAGE_COMBINE = 4,  /* gate-weighted unpermute */
@@ -201,7 +211,8 @@ enum {
   MODSE_STAGE_BWD_DGRAD = 6,/* dH (+SwiGLU backward) and dX_permuted GEMMs */
   MODSE_STAGE_BWD_WGRAD = 7,/* dW1, dW3, dW2 GEMMs */
   MODSE_STAGE_BWD_ROUTER = 8,/* dX gather, d logits, dW_gate */
-  MODSE_N_STAGES = 9
+  MODSE_STAGE_PLAN = 9,     /* device-side tile plans of the two forward GEMMs */
+  MODSE_N_STAGES = 10
 };
 modse_status modse_stage_timing_enable(int on);
 modse_status modse_stage_times(float* ms);

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 MODSE_F32, MODSE_BF16 = 0, 1
-STAGES = ("route", "permute", "up", "down", "combine", "bwd_prep", "bwd_dgrad", "bwd_wgrad", "bwd_router")
+STAGES = ("route", "permute", "up", "down", "combine", "bwd_prep", "bwd_dgrad", "bwd_wgrad", "bwd_router", "plan")
 
 
 class ModseError(RuntimeError):
@@ -166,10 +166,13 @@ class GateExt:
                         _ptr(self.aux_loss))
 
 
-def modse_workspace_size(d_model, d_ff, top_k, dtype, T, need_bwd=False, raise_on_error=True):
+WS_FWD, WS_BWD, WS_FWD_SAVED = 0, 1, 2   # `which` of modse_workspace_size (MODSE_WS_* in include/modse.h)
+
+
+def modse_workspace_size(d_model, d_ff, top_k, dtype, T, which=WS_FWD, raise_on_error=True):
     out = C.c_size_t(0)
     d = _desc(d_model, d_ff, top_k, dtype)
-    code = load_library().modse_workspace_size(C.byref(d), int(T), int(bool(need_bwd)), C.byref(out))
+    code = load_library().modse_workspace_size(C.byref(d), int(T), int(which), C.byref(out))
     _check(code, "modse_workspace_size", raise_on_error)
     return out.value if code == 0 else code
 

@@ -67,9 +67,25 @@ size_t hidden_elems_max(const LayerDims& L) {
   return s * (size_t)L.T;
 }
 
+// scratch of the routing kernels (see RouteBufs)
+struct RouteScratch {
+  size_t blockhist, near_flag, wpad, total;
+};
+void carve_route(Carver& c, const LayerDims& L, modse_dtype dt, RouteScratch& r) {
+  const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
+  r.blockhist = c.take(nb * (L.N + 1) * 4);
+  r.near_flag = c.take((size_t)L.T * 4);
+  r.wpad = c.take(route_wpad_bytes(L, esize_of(dt)));
+  r.total = c.off;
+}
+RouteBufs route_bufs(char* base, const RouteScratch& r) {
+  return RouteBufs{reinterpret_cast<int32_t*>(base + r.blockhist), reinterpret_cast<int32_t*>(base + r.near_flag),
+                   base + r.wpad};
+}
+
 struct FwdLayout {
-  size_t blockhist, near_flag, topk_idx, topk_w, counts, offsets, row_of, src_of, near_tie, plan_up, plan_down, Xp, H, O, Opart,
-      total;
+  RouteScratch route;
+  size_t topk_idx, topk_w, counts, offsets, row_of, src_of, near_tie, plan_up, plan_down, Xp, H, O, Opart, total;
 };
 
 // Decode-sized batches stream the expert weights once; the down-projection then has too few output tiles
@@ -92,13 +108,13 @@ int splitk_max_chunks(const LayerDims& L, int kchunk) {
   return m;
 }
 
-FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
+// with_saved: the call is given the buffer that carries activations to the backward pass; the permuted rows,
+// the hidden activations and the expert outputs then live there and take no workspace
+FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt, bool with_saved) {
   FwdLayout w;
   Carver c;
   const size_t es = esize_of(dt), Tk = (size_t)L.T * L.k;
-  const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
-  w.blockhist = c.take(nb * (L.N + 1) * 4);
-  w.near_flag = c.take((size_t)L.T * 4);
+  carve_route(c, L, dt, w.route);
   w.topk_idx = c.take(Tk * 4);
   w.topk_w = c.take(Tk * 4);
   w.counts = c.take(L.N * 4);
@@ -108,10 +124,10 @@ FwdLayout fwd_layout(const LayerDims& L, modse_dtype dt) {
   w.near_tie = c.take(4);
   w.plan_up = c.take(sizeof(GemmPlan));
   w.plan_down = c.take(sizeof(GemmPlan));
-  w.Xp = c.take(Tk * L.d * es);
-  w.H = c.take(hidden_elems_max(L) * es);
-  w.O = c.take(Tk * L.d * es);
-  const int kchunk = splitk_chunk(L);
+  w.Xp = c.take(with_saved ? 0 : Tk * L.d * es);
+  w.H = c.take(with_saved ? 0 : hidden_elems_max(L) * es);
+  w.O = c.take(with_saved ? 0 : Tk * L.d * es);
+  const int kchunk = with_saved ? 0 : splitk_chunk(L);
   w.Opart = c.take(kchunk ? (size_t)splitk_max_chunks(L, kchunk) * Tk * L.d * 4 : 0);
   w.total = c.off;
   return w;
@@ -252,7 +268,9 @@ modse_status modse_workspace_size(const modse_desc* desc, int64_t T, int need_bw
   const modse_status st = check_desc(desc, T);
   if (st != MODSE_OK) return st;
   const LayerDims L = make_dims(desc, T);
-  *bytes = need_bwd ? bwd_layout(L, desc->dtype).total : fwd_layout(L, desc->dtype).total;
+  if (need_bwd != MODSE_WS_FWD && need_bwd != MODSE_WS_BWD && need_bwd != MODSE_WS_FWD_SAVED) return MODSE_ERR_INVALID_ARG;
+  *bytes = need_bwd == MODSE_WS_BWD ? bwd_layout(L, desc->dtype).total
+                                    : fwd_layout(L, desc->dtype, need_bwd == MODSE_WS_FWD_SAVED).total;
   return MODSE_OK;
 }
 
@@ -280,13 +298,14 @@ modse_status modse_route_ext(const modse_desc* desc, int64_t T, const void* x, c
   GateExtPtrs G;
   if (ext) G = ext_ptrs(ext);
   const LayerDims L = make_dims(desc, T);
-  const FwdLayout w = fwd_layout(L, desc->dtype);
+  RouteScratch w;  // the routing scratch is the head of the forward workspace; this call needs no more of it
+  Carver c;
+  carve_route(c, L, desc->dtype, w);
   if (ws_bytes < w.total) return MODSE_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  char* wsb = static_cast<char*>(ws);
-  const RoutingPtrs R = routing_from(out, wsb, w);
-  HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
-                       reinterpret_cast<int32_t*>(wsb + w.near_flag), nullptr, ext ? &G : nullptr, s));
+  const RoutingPtrs R = {out->topk_idx, out->topk_w, out->counts, out->offsets, out->row_of, out->src_of, out->near_tie_count};
+  HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, route_bufs(static_cast<char*>(ws), w), nullptr,
+                       ext ? &G : nullptr, s));
   return MODSE_OK;
 }
 
@@ -301,19 +320,6 @@ namespace {
 constexpr int kMaxDevices = 64;
 void* g_route_scratch_ptr[kMaxDevices] = {};
 
-// the part of the forward workspace that modse_route uses, laid out as fwd_layout does
-struct RouteScratch {
-  size_t blockhist, near_flag, total;
-};
-RouteScratch route_scratch_layout(const LayerDims& L) {
-  RouteScratch r;
-  Carver c;
-  const size_t nb = ((size_t)L.T + MODSE_ROUTE_TOKENS_PER_BLOCK - 1) / MODSE_ROUTE_TOKENS_PER_BLOCK;
-  r.blockhist = c.take(nb * (L.N + 1) * 4);
-  r.near_flag = c.take((size_t)L.T * 4);
-  r.total = c.off;
-  return r;
-}
 }  // namespace
 
 modse_status modse_route_static(const modse_desc* desc, int64_t T, const void* x, const void* W_gate,
@@ -323,7 +329,9 @@ modse_status modse_route_static(const modse_desc* desc, int64_t T, const void* x
   if (T == 0) return MODSE_OK;
   if (!x || !W_gate || !routing_complete(out)) return MODSE_ERR_INVALID_ARG;
   const LayerDims L = make_dims(desc, T);
-  const RouteScratch w = route_scratch_layout(L);
+  RouteScratch w;
+  Carver c;
+  carve_route(c, L, desc->dtype, w);
   if (w.total > MODSE_ROUTE_STATIC_SCRATCH_BYTES) return MODSE_ERR_WORKSPACE;  // more tokens than the array serves
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MODSE_ERR_HIP;
@@ -335,8 +343,7 @@ modse_status modse_route_static(const modse_desc* desc, int64_t T, const void* x
   char* scratch = static_cast<char*>(g_route_scratch_ptr[dev]);
   const RoutingPtrs R = {out->topk_idx, out->topk_w, out->counts, out->offsets, out->row_of, out->src_of, out->near_tie_count};
   // every word of the scratch that a kernel reads has been written by an earlier kernel of this call
-  HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(scratch + w.blockhist),
-                       reinterpret_cast<int32_t*>(scratch + w.near_flag), nullptr, nullptr,
+  HIP_TRY(launch_route(L, desc->dtype, x, W_gate, logit_bias, R, route_bufs(scratch, w), nullptr, nullptr,
                        static_cast<hipStream_t>(hip_stream)));
   return MODSE_OK;
 }
@@ -372,18 +379,20 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   if (routing_out && !routing_complete(routing_out)) return MODSE_ERR_INVALID_ARG;
   const modse_dtype dt = desc->dtype;
   const LayerDims L = make_dims(desc, T);
-  const FwdLayout w = fwd_layout(L, dt);
+  const FwdLayout w = fwd_layout(L, dt, saved != nullptr);
   if (ws_bytes < w.total) return MODSE_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* wsb = static_cast<char*>(ws);
   const RoutingPtrs R = routing_from(routing_out, wsb, w);
+  const RouteBufs RB = route_bufs(wsb, w.route);
   Stamp stamp(0, s);
 
   // with a backward pass to follow, the permuted rows go straight into the saved buffer
   void* Xp = saved ? static_cast<char*>(saved) + saved_layout(L, dt).Xp : wsb + w.Xp;
-  HIP_TRY(launch_route(L, dt, x, W_gate, logit_bias, R, reinterpret_cast<int32_t*>(wsb + w.blockhist),
-                       reinterpret_cast<int32_t*>(wsb + w.near_flag), Xp, ext ? &G : nullptr, s));
-  stamp.mark(MODSE_STAGE_ROUTE);  // routing and the row scatter share kernels; the scatter is counted here
+  HIP_TRY(launch_router(L, dt, x, W_gate, logit_bias, R, RB, ext ? &G : nullptr, s));
+  stamp.mark(MODSE_STAGE_ROUTE);
+  HIP_TRY(launch_permute(L, dt, x, R, RB, Xp, ext ? &G : nullptr, s));
+  stamp.mark(MODSE_STAGE_PERMUTE);
 
   FwdPlanArgs pa;
   std::memset(&pa, 0, sizeof(pa));
@@ -404,7 +413,7 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   pa.kchunk = kchunk;
   pa.Opart = reinterpret_cast<float*>(wsb + w.Opart);
   HIP_TRY(launch_plan_fwd(L, dt, R.counts, R.offsets, pa, s));
-  stamp.mark(MODSE_STAGE_PERMUTE);
+  stamp.mark(MODSE_STAGE_PLAN);
 
   const int skinny = T <= MODSE_SKINNY_TOKENS;
   HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU, pa.up, 0, saved != nullptr, tiles_bound(L, T, pa.up_tile, true), s, -1,

@@ -139,10 +139,27 @@ struct GateExtPtrs {
 
 // ---------------------------------------------------------------- launchers
 // route.hip
-// near_flag: [T] ints of workspace
+// Scratch of the routing kernels.  wpad is needed only when n_experts is not one of 2, 4, 8, 16, 32, 64: the
+// routers that read the router matrices from memory fetch whole rows with vector loads, so such matrices are
+// first copied into rows of padded_experts(N) columns (W_gate, then W_noise).
+struct RouteBufs {
+  int32_t* blockhist;  // [ceil(T / MODSE_ROUTE_TOKENS_PER_BLOCK), N + 1]
+  int32_t* near_flag;  // [T]
+  void* wpad;          // route_wpad_bytes()
+};
+inline int padded_experts(int N) { return N <= 2 ? 2 : N <= 4 ? 4 : N <= 8 ? 8 : N <= 16 ? 16 : N <= 32 ? 32 : 64; }
+inline size_t route_wpad_bytes(const LayerDims& L, size_t elem_size) {
+  const int NE = padded_experts(L.N);
+  return NE == L.N ? 0 : 2 * (size_t)L.d * NE * elem_size;
+}
+// launch_route = launch_router (logits, top-k, gate) + launch_permute (histogram, scan, stable scatter; Xp may
+// be null).
+hipError_t launch_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
+                         const RoutingPtrs& R, const RouteBufs& B, const GateExtPtrs* G, hipStream_t s);
+hipError_t launch_permute(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, const RouteBufs& B,
+                          void* Xp, const GateExtPtrs* G, hipStream_t s);
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
-                        const RoutingPtrs& R, int32_t* blockhist, int32_t* near_flag, void* Xp, const GateExtPtrs* G,
-                        hipStream_t s);
+                        const RoutingPtrs& R, const RouteBufs& B, void* Xp, const GateExtPtrs* G, hipStream_t s);
 hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,
                                 hipStream_t s);
 hipError_t launch_combine(const LayerDims& L, modse_dtype dt, const void* O, const RoutingPtrs& R, void* y,
@@ -155,7 +172,7 @@ struct BwdRouterBufs {  // workspace of the router's backward pass
   float* dl;           // [T, N] dense gradient of the logits
   float* du;           // [T, N] gradient of x W_noise
   float* dgamma_part;  // [ceil(T / 256)]
-  float* dW_partial;   // [ceil(T / 64), d, N] per-block shares of a router-side weight gradient
+  float* dW_partial;   // [ceil(T / 32), d, N] per-block shares of a router-side weight gradient (32 tokens per block)
 };
 hipError_t launch_bwd_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const void* dXp,
                              const float* dg, const RoutingPtrs& R, const GateExtPtrs* G, float aux_grad,

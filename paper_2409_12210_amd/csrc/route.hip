@@ -4,6 +4,7 @@
 // arXiv 2409.12210).  Logits are accumulated in float64: products of bf16 or fp32 inputs are exact in
 // float64, so the integer routing decision is taken at the same precision as a float64 reference and
 // does not depend on summation order beyond the last bit.
+#include <algorithm>
 #include <climits>
 
 #include "common.h"
@@ -14,6 +15,8 @@ constexpr int TPB = MODSE_ROUTE_TOKENS_PER_BLOCK;  // tokens per block
 constexpr int ROUTE_THREADS = 256;
 constexpr int ROUTER_TOKEN_MAX_T = 4096;  // batches up to this size take router_token_kernel
 constexpr int TOK_PER_WAVE = TPB / (ROUTE_THREADS / 64);  // 8
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline double shfl_xor_f64(double v, int mask) {
   int lo = __double2loint(v), hi = __double2hiint(v);
@@ -24,7 +27,8 @@ __device__ inline double shfl_xor_f64(double v, int mask) {
 
 // Sum each of the V values over the 64 lanes of a wave.  Every halving step sends half of the values to
 // the partner lane and keeps the other half, so V values cost V-1 + (6 - log2 V) shuffles.  On return
-// lane l (l < V) holds in vals[0] the total of value index bitrev_{log2 V}(l).
+// lane l (l < V) holds in vals[0] the total of value index bitrev_{log2 V}(l).  (Template recursion, not
+// loops: every index into vals is then a constant and the array stays in registers for any V.)
 template <int V>
 struct Log2 {
   static constexpr int value = 1 + Log2<V / 2>::value;
@@ -34,22 +38,27 @@ struct Log2<1> {
   static constexpr int value = 0;
 };
 
+template <int W, int I, int BIT, int V>
+__device__ inline void halve_one(double (&vals)[V], bool upper) {
+  if constexpr (I < W) {
+    const double keep = upper ? vals[I + W] : vals[I];
+    const double send = upper ? vals[I] : vals[I + W];
+    vals[I] = keep + shfl_xor_f64(send, BIT);
+    halve_one<W, I + 1, BIT>(vals, upper);
+  }
+}
+template <int LIVE, int BIT, int V>
+__device__ inline void halve_all(double (&vals)[V], int lane) {
+  if constexpr (LIVE > 1) {
+    halve_one<LIVE / 2, 0, BIT>(vals, (lane & BIT) != 0);
+    halve_all<LIVE / 2, BIT * 2>(vals, lane);
+  }
+}
 template <int V>
 __device__ inline void wave_sum_values(double (&vals)[V], int lane) {
-  constexpr int P = Log2<V>::value;
+  halve_all<V, 1>(vals, lane);
 #pragma unroll
-  for (int s = 0; s < P; ++s) {
-    const int width = V >> (s + 1), bit = 1 << s;
-    const bool upper = (lane & bit) != 0;
-#pragma unroll
-    for (int i = 0; i < width; ++i) {
-      const double keep = upper ? vals[i + width] : vals[i];
-      const double send = upper ? vals[i] : vals[i + width];
-      vals[i] = keep + shfl_xor_f64(send, bit);
-    }
-  }
-#pragma unroll
-  for (int s = P; s < 6; ++s) vals[0] += shfl_xor_f64(vals[0], 1 << s);
+  for (int s = Log2<V>::value; s < 6; ++s) vals[0] += shfl_xor_f64(vals[0], 1 << s);
 }
 
 template <int P>
@@ -78,94 +87,219 @@ __device__ inline double softplus_f64(double u) {  // log(1 + exp(u)) without ov
   return u > 0.0 ? u + log1p(exp(-u)) : log1p(exp(u));
 }
 
-// One block routes TPB consecutive tokens.  blockhist[b][0..N-1] = this block's per-expert assignment
-// counts, blockhist[b][N] = its near-tie token count.
-// EXT adds the optional parts of the gate: the noise term RMSNorm(Softplus(x W_n)) of H(x) (Sec. 2 Eq. 4-5;
-// G.Wn != null) and the full-softmax probabilities p(x) that the auxiliary loss needs (Sec. 3.2 Eq. 11;
-// G.probs != null).  Both reuse the x rows this kernel already holds in registers.
-// (Two waves per SIMD are asked for so that the kernel stays within the 256 architectural registers: a
-// variant of it that the compiler let run over into accumulation registers computed wrong sums.)
-template <typename T, int NE, int TOK, bool EXT>
+// KeepTopK on one token's N logits (Sec. 2 Eq. 3), k <= 2: the two largest and the third largest value.  Strict
+// comparisons while scanning upward leave ties with the lower index.  The second pick always differs from the
+// first: when no logit besides the first is above -inf (all others masked out by an infinite negative bias) it is
+// the lowest other index, as in a stable descending sort.
+struct TopPick {
+  double m1, m2, m3;
+  int i1, i2;
+};
+__device__ inline TopPick pick_top(const double* logits, int N) {
+  TopPick p = {-INFINITY, -INFINITY, -INFINITY, 0, -1};
+  for (int e = 0; e < N; ++e) {
+    const double l = logits[e];
+    if (l > p.m1) {
+      p.m3 = p.m2; p.m2 = p.m1; p.i2 = p.i1; p.m1 = l; p.i1 = e;
+    } else if (l > p.m2) {
+      p.m3 = p.m2; p.m2 = l; p.i2 = e;
+    } else if (l > p.m3) {
+      p.m3 = l;
+    }
+  }
+  if (p.i2 < 0 || p.i2 == p.i1) p.i2 = p.i1 == 0 ? 1 : 0;
+  return p;
+}
+// Writes token t's expert indices and gate weights (softmax over the kept logits, Eq. 2); returns whether the
+// gap that decided the selection is under 1e-6.
+__device__ inline bool write_gate(const TopPick& p, int t, int N, int top_k, int32_t* __restrict__ topk_idx,
+                                  float* __restrict__ topk_w) {
+  if (top_k == 2) {
+    const double g1 = 1.0 / (1.0 + exp(p.m2 - p.m1));
+    topk_idx[(size_t)t * 2] = p.i1;
+    topk_idx[(size_t)t * 2 + 1] = p.i2;
+    topk_w[(size_t)t * 2] = (float)g1;
+    topk_w[(size_t)t * 2 + 1] = (float)(1.0 - g1);
+    return (p.m1 - p.m2 < 1e-6) || (N > 2 && p.m2 - p.m3 < 1e-6);
+  }
+  topk_idx[t] = p.i1;
+  topk_w[t] = 1.f;
+  return N > 1 && p.m1 - p.m2 < 1e-6;
+}
+
+// ---------------------------------------------------------------- the router's dot products
+// Both block-wise routers give lane l of a wave the columns 8l..8l+7 of every 512-column step of the token
+// rows: a row is read with one contiguous 1 KiB load per wave and step, and the loads of the next step are
+// issued before the arithmetic of the current one.  A wave holds TOK tokens x EC experts of float64 sums at a
+// time (at most 32, so that sums, the two sets of row registers and one converted matrix row fit the register
+// file without spilling); layers with more experts than EC take the expert columns in chunks.
+
+// eight consecutive elements as loaded, and element i of them as float
+template <typename T>
+struct Raw8;
+template <>
+struct Raw8<bf16_t> {
+  u32x4 v;
+  __device__ void load(const bf16_t* p) { v = *reinterpret_cast<const u32x4*>(p); }
+  __device__ float get(int i) const {
+    const uint32_t w = v[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+};
+template <>
+struct Raw8<float> {
+  f32x4 a, b;
+  __device__ void load(const float* p) {
+    a = *reinterpret_cast<const f32x4*>(p);
+    b = *reinterpret_cast<const f32x4*>(p + 4);
+  }
+  __device__ float get(int i) const { return i < 4 ? a[i] : b[i - 4]; }
+};
+
+// EC columns, from column e0, of row r of a router matrix in memory whose rows are ldw elements apart (ldw
+// is the padded expert count, so a row is a whole number of aligned vectors)
+template <typename T, int EC>
+struct GlobalRows {
+  const T* W;
+  int ldw, e0;
+  __device__ void fetch(int r, float (&wf)[EC]) const { load_row<EC>(W + (size_t)r * ldw + e0, wf); }
+};
+
+// The same from the LDS copy that router_stream_kernel keeps: floats, NE per row; the eight rows of one lane
+// and step lie together, followed by 16 bytes of padding, so that the 16 lanes which a 128-bit LDS read
+// serves together fall into different banks.
+constexpr int rs_group_bytes(int NE) { return 8 * NE * 4 + 16; }
+template <int NE, int EC>
+struct LdsRows {
+  const char* base;
+  int e0;
+  __device__ void fetch(int r, float (&wf)[EC]) const {
+    const char* p = base + (r >> 3) * rs_group_bytes(NE) + (r & 7) * NE * 4 + e0 * 4;
+    if constexpr (EC >= 4) {
+#pragma unroll
+      for (int e = 0; e < EC; e += 4) {
+        const f32x4 q = *reinterpret_cast<const f32x4*>(p + e * 4);
+        wf[e] = q.x; wf[e + 1] = q.y; wf[e + 2] = q.z; wf[e + 3] = q.w;
+      }
+    } else {
+      const f32x2 q = *reinterpret_cast<const f32x2*>(p);
+      wf[0] = q.x; wf[1] = q.y;
+    }
+  }
+};
+
+// acc[tt * EC + e] += sum over this lane's columns c of row[tt][c] * W[c][e0 + e], in float64
+template <typename T, int TOK, int EC, typename Rows>
+__device__ inline void lane_dots(const T* const (&row)[TOK], int d, int lane, const Rows& rows,
+                                 double (&acc)[TOK * EC]) {
+  const int nstep = (d + 511) >> 9;
+  Raw8<T> cur[TOK], nxt[TOK];
+  {
+    const int c = min(lane * 8, d - 8);
+#pragma unroll
+    for (int tt = 0; tt < TOK; ++tt) cur[tt].load(row[tt] + c);
+  }
+  for (int st = 0; st < nstep; ++st) {
+    const int c = st * 512 + lane * 8;
+    const bool more = st + 1 < nstep;
+    if (more) {
+      const int cn = min(c + 512, d - 8);
+#pragma unroll
+      for (int tt = 0; tt < TOK; ++tt) nxt[tt].load(row[tt] + cn);
+    }
+    if (c < d) {
+      float wf[EC];
+      rows.fetch(c, wf);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float wn[EC];
+        if (i < 7) rows.fetch(c + i + 1, wn);  // the next matrix row is on its way during this row's arithmetic
+        double wd[EC];
+#pragma unroll
+        for (int e = 0; e < EC; ++e) wd[e] = (double)wf[e];
+#pragma unroll
+        for (int tt = 0; tt < TOK; ++tt) {
+          const double xd = (double)cur[tt].get(i);
+#pragma unroll
+          for (int e = 0; e < EC; ++e) acc[tt * EC + e] = fma(xd, wd[e], acc[tt * EC + e]);
+        }
+        if (i < 7) {
+#pragma unroll
+          for (int e = 0; e < EC; ++e) wf[e] = wn[e];
+        }
+        // keeps the scheduler from fetching and converting all eight rows ahead of the arithmetic, which
+        // costs more registers than there are
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int tt = 0; tt < TOK; ++tt) cur[tt] = nxt[tt];
+    }
+  }
+}
+
+// tokens x expert columns that a wave sums at a time
+template <int NE>
+struct RouterShape {
+  static constexpr int EC = NE < 16 ? NE : 16;
+  static constexpr int TOK = 32 / EC < 8 ? 32 / EC : 8;
+  static constexpr int V = TOK * EC;
+};
+
+// One wave's TOK tokens against all NE expert columns of one matrix: sums[tt][e] (an LDS array of the wave)
+template <typename T, int NE, typename MakeRows>
+__device__ inline void wave_logits(const T* const (&row)[RouterShape<NE>::TOK], int d, int lane, MakeRows make_rows,
+                                   double (*sums)[NE]) {
+  using S = RouterShape<NE>;
+  constexpr int EC = S::EC, TOK = S::TOK, V = S::V;
+#pragma unroll 1
+  for (int e0 = 0; e0 < NE; e0 += EC) {
+    double acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.0;
+    lane_dots<T, TOK, EC>(row, d, lane, make_rows(e0), acc);
+    wave_sum_values<V>(acc, lane);
+    if (lane < V) {
+      const int v = bitrev<Log2<V>::value>(lane);
+      sums[v / EC][e0 + v % EC] = acc[0];
+    }
+  }
+}
+
+// One block routes TPB consecutive tokens, eight per wave.  blockhist[b][0..N-1] = this block's per-expert
+// assignment counts, blockhist[b][N] = its near-tie token count.  Reads the router matrices from memory (through
+// the caches) for every TOK tokens: the form for layers whose W_gate does not fit router_stream_kernel's LDS
+// area, for small batches with many experts, and for the optional parts of the gate (EXT): the noise term
+// RMSNorm(Softplus(x W_n)) of H(x) (Sec. 2 Eq. 4-5; G.W_noise != null), which takes a second pass over the
+// token rows with W_n in place of W_gate, and the full-softmax probabilities p(x) that the auxiliary loss needs
+// (Sec. 3.2 Eq. 11; G.probs != null).
+template <typename T, int NE, bool EXT>
 __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
-                                                               const float* __restrict__ bias, int ntok, int d, int N,
-                                                               int top_k, int32_t* __restrict__ topk_idx,
-                                                               float* __restrict__ topk_w,
-                                                               int32_t* __restrict__ blockhist, GateExtPtrs G) {
-  constexpr int V = NE * TOK;
-  __shared__ double s_logit[ROUTE_THREADS / 64][TOK][NE];
-  __shared__ double s_u[EXT ? ROUTE_THREADS / 64 : 1][EXT ? TOK : 1][EXT ? NE : 1];
+                                                              const float* __restrict__ bias, int ntok, int d, int N,
+                                                              int top_k, int32_t* __restrict__ topk_idx,
+                                                              float* __restrict__ topk_w,
+                                                              int32_t* __restrict__ blockhist, GateExtPtrs G) {
+  constexpr int TOK = RouterShape<NE>::TOK, EC = RouterShape<NE>::EC;
+  constexpr int WAVES = ROUTE_THREADS / 64;
+  __shared__ double s_logit[WAVES][TOK][NE];
+  __shared__ double s_u[EXT ? WAVES : 1][EXT ? TOK : 1][EXT ? NE : 1];
   __shared__ int s_hist[MODSE_MAX_EXPERTS + 1];
   const T* Wn = EXT ? static_cast<const T*>(G.W_noise) : nullptr;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tok0 = blockIdx.x * TPB + wave * TOK_PER_WAVE;
   if (tid <= N) s_hist[tid] = 0;
   __syncthreads();
 
   for (int pass = 0; pass < TOK_PER_WAVE / TOK; ++pass) {
     const int tbase = tok0 + pass * TOK;
-    double acc[V], acc2[EXT ? V : 1];
+    const T* row[TOK];
 #pragma unroll
-    for (int i = 0; i < V; ++i) acc[i] = 0.0;
-    if (EXT) {
-#pragma unroll
-      for (int i = 0; i < V; ++i) acc2[EXT ? i : 0] = 0.0;
-    }
-    for (int c = lane * 8; c < d; c += 64 * 8) {
-      float xv[TOK][8];
-#pragma unroll
-      for (int tt = 0; tt < TOK; ++tt) {
-        const int t = min(tbase + tt, ntok - 1);  // rows past the end repeat the last token; never written
-        load8(x + (size_t)t * d + c, xv[tt]);
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {  // one W_gate row at a time keeps the register footprint small
-        double xd[TOK];
-#pragma unroll
-        for (int tt = 0; tt < TOK; ++tt) xd[tt] = (double)xv[tt][i];
-        const T* wrow = Wg + (size_t)(c + i) * N;
-        float wf[NE];
-        if (N == NE) {
-          load_row<NE>(wrow, wf);  // one vector load per W_gate row
-        } else {  // columns e >= N repeat the last expert; their sums are never looked at
-#pragma unroll
-          for (int e = 0; e < NE; ++e) wf[e] = (float)wrow[min(e, N - 1)];
-        }
-#pragma unroll
-        for (int e = 0; e < NE; ++e) {
-          const double wd = (double)wf[e];
-#pragma unroll
-          for (int tt = 0; tt < TOK; ++tt) acc[tt * NE + e] = fma(xd[tt], wd, acc[tt * NE + e]);
-        }
-        if (EXT && Wn) {  // the same x values against the noise matrix
-          const T* nrow = Wn + (size_t)(c + i) * N;
-          if (N == NE) {
-            load_row<NE>(nrow, wf);
-          } else {
-#pragma unroll
-            for (int e = 0; e < NE; ++e) wf[e] = (float)nrow[min(e, N - 1)];
-          }
-#pragma unroll
-          for (int e = 0; e < NE; ++e) {
-            const double wd = (double)wf[e];
-#pragma unroll
-            for (int tt = 0; tt < TOK; ++tt) acc2[EXT ? tt * NE + e : 0] = fma(xd[tt], wd, acc2[EXT ? tt * NE + e : 0]);
-          }
-        }
-      }
-    }
-    wave_sum_values<V>(acc, lane);
-    if (lane < V) {
-      const int v = bitrev<Log2<V>::value>(lane);
-      s_logit[wave][v / NE][v % NE] = acc[0];
-    }
+    for (int tt = 0; tt < TOK; ++tt)  // rows past the end repeat the last token; never written
+      row[tt] = x + (size_t)min(tbase + tt, ntok - 1) * d;
+    wave_logits<T, NE>(row, d, lane, [&](int e0) { return GlobalRows<T, EC>{Wg, NE, e0}; }, s_logit[wave]);
     if constexpr (EXT) {
-      if (Wn) {
-        wave_sum_values<V>(acc2, lane);
-        if (lane < V) {
-          const int v = bitrev<Log2<V>::value>(lane);
-          s_u[wave][v / NE][v % NE] = acc2[0];
-        }
-      }
+      if (Wn) wave_logits<T, NE>(row, d, lane, [&](int e0) { return GlobalRows<T, EC>{Wn, NE, e0}; }, s_u[wave]);
     }
     __syncthreads();
     if (lane < TOK && tbase + lane < ntok) {
@@ -186,46 +320,91 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_kernel(const T* __res
           for (int e = 0; e < N; ++e) s_logit[wave][lane][e] += scale * s_u[wave][lane][e];
         }
       }
-      double m1 = -INFINITY, m2 = -INFINITY, m3 = -INFINITY;
-      int i1 = 0, i2 = 0;
-      for (int e = 0; e < N; ++e) {
-        const double l = s_logit[wave][lane][e];
-        if (l > m1) {  // strict comparisons while scanning upward: ties stay with the lower index
-          m3 = m2; m2 = m1; i2 = i1; m1 = l; i1 = e;
-        } else if (l > m2) {
-          m3 = m2; m2 = l; i2 = e;
-        } else if (l > m3) {
-          m3 = l;
-        }
-      }
-      bool near;
-      if (top_k == 2) {
-        const double g1 = 1.0 / (1.0 + exp(m2 - m1));  // softmax over the two kept logits
-        topk_idx[(size_t)t * 2] = i1;
-        topk_idx[(size_t)t * 2 + 1] = i2;
-        topk_w[(size_t)t * 2] = (float)g1;
-        topk_w[(size_t)t * 2 + 1] = (float)(1.0 - g1);
-        atomicAdd(&s_hist[i1], 1);
-        atomicAdd(&s_hist[i2], 1);
-        near = (m1 - m2 < 1e-6) || (N > 2 && m2 - m3 < 1e-6);
-      } else {
-        topk_idx[t] = i1;
-        topk_w[t] = 1.f;
-        atomicAdd(&s_hist[i1], 1);
-        near = (N > 1 && m1 - m2 < 1e-6);
-      }
+      const TopPick p = pick_top(s_logit[wave][lane], N);
+      const bool near = write_gate(p, t, N, top_k, topk_idx, topk_w);
+      atomicAdd(&s_hist[p.i1], 1);
+      if (top_k == 2) atomicAdd(&s_hist[p.i2], 1);
       if (near) atomicAdd(&s_hist[N], 1);
       if constexpr (EXT) {
         if (G.probs) {  // p(x) = softmax over all N logits
           double den = 0.0;
-          for (int e = 0; e < N; ++e) den += exp(s_logit[wave][lane][e] - m1);
-          for (int e = 0; e < N; ++e) G.probs[(size_t)t * N + e] = (float)(exp(s_logit[wave][lane][e] - m1) / den);
+          for (int e = 0; e < N; ++e) den += exp(s_logit[wave][lane][e] - p.m1);
+          for (int e = 0; e < N; ++e) G.probs[(size_t)t * N + e] = (float)(exp(s_logit[wave][lane][e] - p.m1) / den);
         }
       }
     }
     __syncthreads();
   }
   if (tid <= N) blockhist[(size_t)blockIdx.x * (N + 1) + tid] = s_hist[tid];
+}
+
+// Router for large batches without the optional gate parts.  One 512-thread block per CU copies W_gate into LDS
+// once, as floats (exact for both input types), and then walks over groups of 64 tokens (two histogram blocks of
+// TPB tokens), eight tokens per wave: the matrix rows then cost an LDS read instead of a trip through the
+// vector memory pipeline per TOK tokens, which is what holds router_kernel back.  Sums are float64 FMAs in a
+// fixed order per lane, then wave_sum_values: results do not depend on timing.
+constexpr int RS_THREADS = 512, RS_WAVES = RS_THREADS / 64, RS_TOKENS = 64;
+constexpr int RS_W_BYTES = 136 * 1024;
+
+template <typename T, int NE>
+__global__ __launch_bounds__(RS_THREADS) void router_stream_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
+                                                                  const float* __restrict__ bias, int ntok, int d,
+                                                                  int N, int top_k, int32_t* __restrict__ topk_idx,
+                                                                  float* __restrict__ topk_w,
+                                                                  int32_t* __restrict__ blockhist) {
+  constexpr int TOK = RouterShape<NE>::TOK, EC = RouterShape<NE>::EC;
+  constexpr int GB = rs_group_bytes(NE);
+  constexpr int HW = MODSE_MAX_EXPERTS + 1;
+  __shared__ __attribute__((aligned(16))) char s_w[RS_W_BYTES];
+  __shared__ double s_logit[RS_WAVES][TOK][NE];
+  __shared__ int s_hist[2 * HW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  for (int r = tid; r < d; r += RS_THREADS) {  // W_gate -> LDS; columns past N read as zero
+    float wf[NE];
+    if (N == NE) {
+      load_row<NE>(Wg + (size_t)r * N, wf);
+    } else {
+#pragma unroll
+      for (int e = 0; e < NE; ++e) wf[e] = e < N ? (float)Wg[(size_t)r * N + e] : 0.f;
+    }
+    float* dst = reinterpret_cast<float*>(s_w + (r >> 3) * GB + (r & 7) * NE * 4);
+#pragma unroll
+    for (int e = 0; e < NE; ++e) dst[e] = wf[e];
+  }
+  if (tid < 2 * HW) s_hist[tid] = 0;
+  __syncthreads();
+
+  const int ngroups = (ntok + RS_TOKENS - 1) / RS_TOKENS;
+  const int nhist = (ntok + TPB - 1) / TPB;
+  for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+    for (int pass = 0; pass < 8 / TOK; ++pass) {
+      const int tbase = grp * RS_TOKENS + wave * 8 + pass * TOK;
+      const T* row[TOK];
+#pragma unroll
+      for (int tt = 0; tt < TOK; ++tt)  // rows past the end repeat the last token; never written
+        row[tt] = x + (size_t)min(tbase + tt, ntok - 1) * d;
+      wave_logits<T, NE>(row, d, lane, [&](int e0) { return LdsRows<NE, EC>{s_w, e0}; }, s_logit[wave]);
+      __syncthreads();
+      if (lane < TOK && tbase + lane < ntok) {
+        const int t = tbase + lane;
+        if (bias)
+          for (int e = 0; e < N; ++e) s_logit[wave][lane][e] += (double)bias[e];
+        const TopPick p = pick_top(s_logit[wave][lane], N);
+        const bool near = write_gate(p, t, N, top_k, topk_idx, topk_w);
+        int* hist = s_hist + (wave >> 2) * HW;  // waves 0-3 hold the group's first TPB tokens
+        atomicAdd(&hist[p.i1], 1);
+        if (top_k == 2) atomicAdd(&hist[p.i2], 1);
+        if (near) atomicAdd(&hist[N], 1);
+      }
+      __syncthreads();
+    }
+    if (tid < 2 * HW) {  // the thread that writes a counter out also clears it for the next group
+      const int h = tid / HW, i = tid % HW, b = grp * 2 + h;
+      if (i <= N && b < nhist) blockhist[(size_t)b * (N + 1) + i] = s_hist[tid];
+      s_hist[tid] = 0;
+    }
+  }
 }
 
 // Router without the optional gate parts: one block per G tokens, the 256 threads split the d columns, so
@@ -255,22 +434,24 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_token_kernel(const T*
     float xv[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g) load8(x + (size_t)min(t0 + g, ntok - 1) * d + c, xv[g]);  // (clamped rows: never written)
+    const GlobalRows<T, NE> rows = {Wg, NE, 0};
+    float wf[NE];
+    rows.fetch(c, wf);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const T* wrow = Wg + (size_t)(c + i) * N;
-      float wf[NE];
-      if (N == NE) {
-        load_row<NE>(wrow, wf);
-      } else {
-#pragma unroll
-        for (int e = 0; e < NE; ++e) wf[e] = (float)wrow[min(e, N - 1)];
-      }
+      float wn[NE];
+      if (i < 7) rows.fetch(c + i + 1, wn);
 #pragma unroll
       for (int e = 0; e < NE; ++e) {
         const double wd = (double)wf[e];
 #pragma unroll
         for (int g = 0; g < G; ++g) acc[g * NE + e] = fma((double)xv[g][i], wd, acc[g * NE + e]);
       }
+      if (i < 7) {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) wf[e] = wn[e];
+      }
+      __builtin_amdgcn_sched_barrier(0);  // (see lane_dots)
     }
   }
 #pragma unroll
@@ -294,32 +475,8 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_token_kernel(const T*
   __syncthreads();
   if (tid < G && t0 + tid < ntok) {
     const int t = t0 + tid;
-    double m1 = -INFINITY, m2 = -INFINITY, m3 = -INFINITY;
-    int i1 = 0, i2 = 0;
-    for (int e = 0; e < N; ++e) {
-      const double l = s_logit[tid][e];
-      if (l > m1) {  // strict comparisons while scanning upward: ties stay with the lower index
-        m3 = m2; m2 = m1; i2 = i1; m1 = l; i1 = e;
-      } else if (l > m2) {
-        m3 = m2; m2 = l; i2 = e;
-      } else if (l > m3) {
-        m3 = l;
-      }
-    }
-    bool near;
-    if (top_k == 2) {
-      const double g1 = 1.0 / (1.0 + exp(m2 - m1));  // softmax over the two kept logits
-      topk_idx[(size_t)t * 2] = i1;
-      topk_idx[(size_t)t * 2 + 1] = i2;
-      topk_w[(size_t)t * 2] = (float)g1;
-      topk_w[(size_t)t * 2 + 1] = (float)(1.0 - g1);
-      near = (m1 - m2 < 1e-6) || (N > 2 && m2 - m3 < 1e-6);
-    } else {
-      topk_idx[t] = i1;
-      topk_w[t] = 1.f;
-      near = (N > 1 && m1 - m2 < 1e-6);
-    }
-    near_flag[t] = near ? 1 : 0;
+    const TopPick p = pick_top(s_logit[tid], N);
+    near_flag[t] = write_gate(p, t, N, top_k, topk_idx, topk_w) ? 1 : 0;
   }
 }
 
@@ -706,6 +863,7 @@ __global__ __launch_bounds__(256) void gate_bwd_kernel(const float* __restrict__
 // A thread owns 8 columns of d for all tokens of the block, keeps the 8 x 8 slice of W and of the partial in
 // registers, and per token reads x and the dXp rows once (16-byte loads, a full row per block instruction).
 constexpr int BR_TOK = 32;
+static_assert(BR_TOK == MODSE_ROUTE_TOKENS_PER_BLOCK, "the workspace holds one partial gradient per 32-token block");
 template <typename T>
 __global__ __launch_bounds__(ROUTE_THREADS) void bwd_gate_rows_kernel(
     const T* __restrict__ x, const T* __restrict__ W, int ldw, int e0, int ne, const T* __restrict__ dXp,
@@ -810,63 +968,131 @@ __global__ __launch_bounds__(256) void dwg_reduce_kernel(const float* __restrict
   }
 }
 
-template <typename T, int NE, int TOK>
+// [d, N] -> [d, NE] with zero columns behind the N real ones
+template <typename T>
+__global__ __launch_bounds__(256) void pad_rows_kernel(const T* __restrict__ W, int d, int N, int NE,
+                                                       T* __restrict__ out) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d * NE) return;
+  const int r = i / NE, e = i % NE;
+  out[i] = e < N ? W[(size_t)r * N + e] : (T)0.f;
+}
+
+template <typename T, int NE>
 hipError_t run_router(const LayerDims& L, const T* x, const T* Wg, const float* bias, const RoutingPtrs& R,
                       int32_t* blockhist, const GateExtPtrs* G, hipStream_t s) {
   const int nb = (L.T + TPB - 1) / TPB;
-  if (G)  // two accumulator sets: half the tokens per pass keeps them in registers
-    hipLaunchKernelGGL((router_kernel<T, NE, (TOK > 1 ? TOK / 2 : 1), true>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d,
-                       L.N, L.k, R.topk_idx, R.topk_w, blockhist, *G);
+  if (G)
+    hipLaunchKernelGGL((router_kernel<T, NE, true>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d, L.N,
+                       L.k, R.topk_idx, R.topk_w, blockhist, *G);
   else
-    hipLaunchKernelGGL((router_kernel<T, NE, TOK, false>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d,
-                       L.N, L.k, R.topk_idx, R.topk_w, blockhist, GateExtPtrs{});
+    hipLaunchKernelGGL((router_kernel<T, NE, false>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, Wg, bias, L.T, L.d, L.N,
+                       L.k, R.topk_idx, R.topk_w, blockhist, GateExtPtrs{});
   return hipGetLastError();
 }
 
+// Which router a layer takes.  Plain gate, small and medium batches: one block per token keeps the chip busy
+// where 32-token blocks would leave most CUs idle (measured at d = 2048..4096: 0.04 ms instead of 0.11 ms for 64
+// tokens).  Larger plain batches: router_stream_kernel when W_gate fits its LDS area.  Otherwise, and with the
+// optional gate parts, router_kernel.
+enum RouterKind { ROUTER_TOKEN, ROUTER_STREAM, ROUTER_BLOCK };
+RouterKind router_kind(const LayerDims& L, const GateExtPtrs* G) {
+  if (G) return ROUTER_BLOCK;
+  if (L.N <= 16 && L.T <= ROUTER_TOKEN_MAX_T) return ROUTER_TOKEN;
+  if ((size_t)(L.d / 8) * rs_group_bytes(padded_experts(L.N)) <= (size_t)RS_W_BYTES && L.T >= 1024) return ROUTER_STREAM;
+  return ROUTER_BLOCK;
+}
+
+// logits, top-k, gate (and, except for ROUTER_TOKEN, the block histograms)
 template <typename T>
-hipError_t route_typed(const LayerDims& L, const void* xv, const void* Wgv, const float* bias, const RoutingPtrs& R,
-                       int32_t* blockhist, int32_t* near_flag, void* Xpv, const GateExtPtrs* G, hipStream_t s) {
+hipError_t router_typed(const LayerDims& L, const void* xv, const void* Wgv, const float* bias, const RoutingPtrs& R,
+                        const RouteBufs& B, const GateExtPtrs* G, hipStream_t s) {
   const T* x = static_cast<const T*>(xv);
   const T* Wg = static_cast<const T*>(Wgv);
   hipError_t e;
-  // Plain gate, small and medium batches: one block per token keeps the chip busy where router_kernel's
-  // 32-token blocks would leave most CUs idle (measured at d = 2048..4096: 0.04 ms instead of 0.11 ms for 64
-  // tokens; beyond a few thousand tokens router_kernel's sharing of the matrix rows wins).
-  if (!G && L.N <= 16 && L.T <= ROUTER_TOKEN_MAX_T) {
+  const RouterKind kind = router_kind(L, G);
+  const int NE = padded_experts(L.N);
+  GateExtPtrs Gp;
+  if (G) Gp = *G;
+  if (kind != ROUTER_STREAM && NE != L.N) {  // these kernels want matrix rows of NE elements
+    T* pad = static_cast<T*>(B.wpad);
+    const int nblk = (L.d * NE + 255) / 256;
+    hipLaunchKernelGGL((pad_rows_kernel<T>), dim3(nblk), dim3(256), 0, s, Wg, L.d, L.N, NE, pad);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    Wg = pad;
+    if (G && G->W_noise) {
+      T* pad2 = pad + (size_t)L.d * NE;
+      hipLaunchKernelGGL((pad_rows_kernel<T>), dim3(nblk), dim3(256), 0, s, static_cast<const T*>(G->W_noise), L.d,
+                         L.N, NE, pad2);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      Gp.W_noise = pad2;
+    }
+  }
+  if (kind == ROUTER_TOKEN) {
     const dim3 grid(L.T), blk(ROUTE_THREADS);
 #define MODSE_LAUNCH_TOKEN_ROUTER(NE_)                                                                           \
   hipLaunchKernelGGL((router_token_kernel<T, NE_, 1>), grid, blk, 0, s, x, Wg, bias, L.T, L.d, L.N, L.k, R.topk_idx, \
-                     R.topk_w, near_flag)
-    if (L.N <= 2) MODSE_LAUNCH_TOKEN_ROUTER(2);
-    else if (L.N <= 4) MODSE_LAUNCH_TOKEN_ROUTER(4);
-    else if (L.N <= 8) MODSE_LAUNCH_TOKEN_ROUTER(8);
+                     R.topk_w, B.near_flag)
+    if (NE == 2) MODSE_LAUNCH_TOKEN_ROUTER(2);
+    else if (NE == 4) MODSE_LAUNCH_TOKEN_ROUTER(4);
+    else if (NE == 8) MODSE_LAUNCH_TOKEN_ROUTER(8);
     else MODSE_LAUNCH_TOKEN_ROUTER(16);
 #undef MODSE_LAUNCH_TOKEN_ROUTER
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(route_hist_kernel, dim3((L.T + TPB - 1) / TPB), dim3(64), 0, s, R.topk_idx, near_flag, L.T, L.N,
-                       L.k, blockhist);
     e = hipGetLastError();
-  } else
-  if (L.N <= 2) e = run_router<T, 2, 4>(L, x, Wg, bias, R, blockhist, G, s);
-  else if (L.N <= 4) e = run_router<T, 4, 4>(L, x, Wg, bias, R, blockhist, G, s);
-  else if (L.N <= 8) e = run_router<T, 8, 2>(L, x, Wg, bias, R, blockhist, G, s);
-  else if (L.N <= 16) e = run_router<T, 16, 1>(L, x, Wg, bias, R, blockhist, G, s);
-  else if (L.N <= 32) e = run_router<T, 32, 1>(L, x, Wg, bias, R, blockhist, G, s);
-  else e = run_router<T, 64, 1>(L, x, Wg, bias, R, blockhist, G, s);
+  } else if (kind == ROUTER_STREAM) {
+    const int ngroups = (L.T + RS_TOKENS - 1) / RS_TOKENS;
+    const dim3 grid(std::min(ngroups, 256)), blk(RS_THREADS);  // one block per CU holds the LDS copy of W_gate
+#define MODSE_LAUNCH_STREAM_ROUTER(NE_)                                                                          \
+  hipLaunchKernelGGL((router_stream_kernel<T, NE_>), grid, blk, 0, s, x, Wg, bias, L.T, L.d, L.N, L.k, R.topk_idx, \
+                     R.topk_w, B.blockhist)
+    switch (NE) {
+      case 2: MODSE_LAUNCH_STREAM_ROUTER(2); break;
+      case 4: MODSE_LAUNCH_STREAM_ROUTER(4); break;
+      case 8: MODSE_LAUNCH_STREAM_ROUTER(8); break;
+      case 16: MODSE_LAUNCH_STREAM_ROUTER(16); break;
+      case 32: MODSE_LAUNCH_STREAM_ROUTER(32); break;
+      default: MODSE_LAUNCH_STREAM_ROUTER(64); break;
+    }
+#undef MODSE_LAUNCH_STREAM_ROUTER
+    e = hipGetLastError();
+  } else {
+    const GateExtPtrs* g = G ? &Gp : nullptr;
+    switch (NE) {
+      case 2: e = run_router<T, 2>(L, x, Wg, bias, R, B.blockhist, g, s); break;
+      case 4: e = run_router<T, 4>(L, x, Wg, bias, R, B.blockhist, g, s); break;
+      case 8: e = run_router<T, 8>(L, x, Wg, bias, R, B.blockhist, g, s); break;
+      case 16: e = run_router<T, 16>(L, x, Wg, bias, R, B.blockhist, g, s); break;
+      case 32: e = run_router<T, 32>(L, x, Wg, bias, R, B.blockhist, g, s); break;
+      default: e = run_router<T, 64>(L, x, Wg, bias, R, B.blockhist, g, s); break;
+    }
+  }
   if (e != hipSuccess) return e;
-  const int nb = (L.T + TPB - 1) / TPB;
-  hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(256), 0, s, blockhist, nb, L.N, R.counts, R.offsets,
-                     R.near_tie_count);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((scatter_kernel<T>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, L.T, L.d, L.N, L.k, R.topk_idx,
-                     R.offsets, blockhist, R.row_of, R.src_of, static_cast<T*>(Xpv));
-  if ((e = hipGetLastError()) != hipSuccess) return e;
   if (G && G->probs) {
     hipLaunchKernelGGL(aux_finish_kernel, dim3(1), dim3(256), 0, s, G->probs, R.topk_idx, L.T, L.N, L.k, G->alpha,
                        G->aux_f, G->aux_P, G->aux_loss);
     e = hipGetLastError();
   }
   return e;
+}
+
+// histogram (where the router has not made it), scan over blocks, stable scatter
+template <typename T>
+hipError_t permute_typed(const LayerDims& L, const void* xv, const RoutingPtrs& R, const RouteBufs& B, void* Xpv,
+                         const GateExtPtrs* G, hipStream_t s) {
+  const T* x = static_cast<const T*>(xv);
+  const int nb = (L.T + TPB - 1) / TPB;
+  hipError_t e;
+  if (router_kind(L, G) == ROUTER_TOKEN) {
+    hipLaunchKernelGGL(route_hist_kernel, dim3(nb), dim3(64), 0, s, R.topk_idx, B.near_flag, L.T, L.N, L.k,
+                       B.blockhist);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(256), 0, s, B.blockhist, nb, L.N, R.counts, R.offsets,
+                     R.near_tie_count);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((scatter_kernel<T>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, L.T, L.d, L.N, L.k, R.topk_idx,
+                     R.offsets, B.blockhist, R.row_of, R.src_of, static_cast<T*>(Xpv));
+  return hipGetLastError();
 }
 
 // dX and the gradient of one router-side matrix, 8 expert columns per launch
@@ -889,11 +1115,21 @@ hipError_t gate_rows_typed(const LayerDims& L, const void* x, const void* W, con
 
 }  // namespace
 
+hipError_t launch_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
+                         const RoutingPtrs& R, const RouteBufs& B, const GateExtPtrs* G, hipStream_t s) {
+  return dt == MODSE_F32 ? router_typed<float>(L, x, W_gate, bias, R, B, G, s)
+                         : router_typed<bf16_t>(L, x, W_gate, bias, R, B, G, s);
+}
+
+hipError_t launch_permute(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, const RouteBufs& B,
+                          void* Xp, const GateExtPtrs* G, hipStream_t s) {
+  return dt == MODSE_F32 ? permute_typed<float>(L, x, R, B, Xp, G, s) : permute_typed<bf16_t>(L, x, R, B, Xp, G, s);
+}
+
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
-                        const RoutingPtrs& R, int32_t* blockhist, int32_t* near_flag, void* Xp, const GateExtPtrs* G,
-                        hipStream_t s) {
-  return dt == MODSE_F32 ? route_typed<float>(L, x, W_gate, bias, R, blockhist, near_flag, Xp, G, s)
-                         : route_typed<bf16_t>(L, x, W_gate, bias, R, blockhist, near_flag, Xp, G, s);
+                        const RoutingPtrs& R, const RouteBufs& B, void* Xp, const GateExtPtrs* G, hipStream_t s) {
+  const hipError_t e = launch_router(L, dt, x, W_gate, bias, R, B, G, s);
+  return e != hipSuccess ? e : launch_permute(L, dt, x, R, B, Xp, G, s);
 }
 
 hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,

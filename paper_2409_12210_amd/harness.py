@@ -44,9 +44,11 @@ class LayerRunner:
         self.need_bwd = need_bwd
         self.routing = B.Routing.empty(max(self.T, 1), self.N, self.k, device)
         self.y = torch.empty((self.T, self.d), dtype=self.tdtype, device=device)
-        ws_bytes = B.modse_workspace_size(self.d, self.d_ff, self.k, dtype, self.T, False)
-        if need_bwd:
-            ws_bytes = max(ws_bytes, B.modse_workspace_size(self.d, self.d_ff, self.k, dtype, self.T, True))
+        if need_bwd:  # the forward call is given `saved`: a small workspace
+            ws_bytes = max(B.modse_workspace_size(self.d, self.d_ff, self.k, dtype, self.T, B.WS_FWD_SAVED),
+                           B.modse_workspace_size(self.d, self.d_ff, self.k, dtype, self.T, B.WS_BWD))
+        else:
+            ws_bytes = B.modse_workspace_size(self.d, self.d_ff, self.k, dtype, self.T, B.WS_FWD)
         self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=device)
         self.saved = None
         if need_bwd:
@@ -105,6 +107,8 @@ class LayerRunner:
 
     def fwd(self, with_routing=True, save=None):
         save = self.need_bwd if save is None else save
+        if bool(save) != bool(self.need_bwd):
+            raise ValueError("the workspace of this runner was sized for save == need_bwd")
         if getattr(self, "ext", None) is not None:
             B.modse_layer_fwd_ext(*self._args(), self.x, self.W_gate, self.bias, self.ext, self.W1, self.W3, self.W2,
                                   self.y, self.routing if with_routing else None, self.saved if save else None,

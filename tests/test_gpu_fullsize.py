@@ -88,15 +88,17 @@ def test_c3_decode_shape_all_tokens():
     assert max_rel(to_host(r.y), y_ref) <= TOL["bf16"]
 
 
-def test_c4_training_step_full_size():
+def check_training_step(cfg, inp, r):
+    """Forward + backward at full size: routing in full, y on a token sample, dX and dW_gate in full, and of the
+    expert weight gradients one hidden unit out of every 256 (the weight-gradient GEMMs tile the hidden units
+    in blocks of 256, so every tile of every expert is touched), plus each expert's first and last unit."""
     from paper_2409_12210_amd.harness import to_host
-    cfg, inp, r = run_config("C4", need_bwd=True)
     idx, _ = check_routing_full(cfg, inp, r.routing_host())
     check_y_sample(cfg, inp, r, idx)
     tol = TOL["bf16"]
     # dX and dW_gate in full (needs the forward of every token in fp64: a few tens of seconds of BLAS)
-    g = orc.layer_bwd(inp.x, inp.W_gate, inp.W1, inp.W3, inp.W2, cfg.d_ff, cfg.top_k, inp.dY, topk_idx=idx,
-                      need_weight_grads=False)
+    g = orc.layer_bwd(inp.x, inp.W_gate, inp.W1, inp.W3, inp.W2, cfg.d_ff, cfg.top_k, inp.dY, inp.logit_bias,
+                      topk_idx=idx, need_weight_grads=False)
     assert max_rel(to_host(r.dX), g.dX) <= tol
     assert max_rel(to_host(r.dW_gate), g.dW_gate) <= tol
     # exact slices of the expert weight gradients; tolerance relative to the largest entry seen
@@ -106,15 +108,37 @@ def test_c4_training_step_full_size():
     rng = np.random.Generator(np.random.Philox(key=99))
     worst = {"dW1": 0.0, "dW3": 0.0, "dW2": 0.0}
     for e, f in enumerate(cfg.d_ff):
-        cols = np.sort(rng.choice(f, size=6, replace=False))
-        cols[0], cols[-1] = 0, f - 1
+        cols = np.array([rng.integers(lo, min(lo + 256, f)) for lo in range(0, f, 256)] + [0, f - 1])
+        cols = np.unique(cols)
         g1, g3, g2 = orc.wgrad_columns(inp.x, inp.W_gate, inp.W1, inp.W3, inp.W2, cfg.d_ff, cfg.top_k, inp.dY, e, cols,
-                                       topk_idx=idx)
+                                       inp.logit_bias, topk_idx=idx)
         worst["dW1"] = max(worst["dW1"], max_rel(dW1[foff[e]:foff[e + 1]][cols], g1))
         worst["dW3"] = max(worst["dW3"], max_rel(dW3[foff[e]:foff[e + 1]][cols], g3))
         worst["dW2"] = max(worst["dW2"], max_rel(dW2[d * foff[e]:d * foff[e + 1]].reshape(d, f)[:, cols], g2))
     for name, err in worst.items():
         assert err <= tol, (name, err)
+
+
+def test_c4_training_step_full_size():
+    cfg, inp, r = run_config("C4", need_bwd=True)
+    check_training_step(cfg, inp, r)
+
+
+def test_c2_training_step_full_size():
+    """Backward under skewed routing: the weight-gradient GEMMs' K (tokens per expert) then ranges over more
+    than a factor of ten between experts."""
+    bias = wl.load_bias_fixture(os.path.join(ROOT, "tests", "golden", "zipf_bias_C2.txt"))
+    cfg, inp, r = run_config("C2", need_bwd=True, bias=bias)
+    counts = r.routing_host()["counts"]
+    assert counts.max() > 8 * counts.min()
+    check_training_step(cfg, inp, r)
+
+
+def test_p700_forward_full_size():
+    """The 9:1 width pairs of the paper's 700M model (Table 2) at 16384 tokens."""
+    cfg, inp, r = run_config("P700")
+    idx, _ = check_routing_full(cfg, inp, r.routing_host())
+    check_y_sample(cfg, inp, r, idx)
 
 
 def test_c1_gate_extensions_and_statistics_full_size():

@@ -43,8 +43,11 @@ CASES = [
     ("n16", 128, (64,) * 16, 333, "f32", 2),
     ("n3", 96, (32, 64, 96), 130, "bf16", 2),
     ("n32", 64, (32,) * 32, 150, "f32", 2),
+    ("n64_f32", 64, (32,) * 64, 203, "f32", 2),
+    ("n64_bf16", 96, (32,) * 64, 333, "bf16", 2),
+    ("n40_bf16", 64, (32,) * 40, 97, "bf16", 2),
 ]
-LAYER_CASES = CASES[:4] + CASES[-1:]
+LAYER_CASES = CASES[:4] + CASES[5:8]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
@@ -93,6 +96,7 @@ def test_layer_fwd_bwd_ext_parity(case, noise, aux):
     assert max_rel(host(r.dX), G.dX) <= tol
     assert max_rel(host(r.dW_gate), G.dW_gate) <= tol
     assert max_rel(host(r.dW1), G.dW1) <= tol
+    assert max_rel(host(r.dW3), G.dW3) <= tol
     assert max_rel(host(r.dW2), G.dW2) <= tol
     if noise:
         assert max_rel(host(r.dW_noise), G.dW_noise) <= tol

@@ -66,6 +66,23 @@ ROUTE_CASES = [
     ("decode_n3", 96, (32, 64, 96), 64, "bf16", 2),
     ("decode_top1", 256, (128, 384, 192, 320), 33, "bf16", 1),
     ("decode_wide", 4096, (64, 192, 128, 128, 64, 192, 128, 128), 64, "bf16", 2),
+    # batches beyond 4096 tokens (or with more than 16 experts, from 1024 tokens) take the router that keeps
+    # W_gate in LDS: every padded expert count, both dtypes, ragged token counts, several groups per block
+    ("stream_n8", 256, (128, 384, 192, 320, 224, 288, 256, 256), 5000, "bf16", 2),
+    ("stream_n8_f32", 256, (128, 384, 192, 320, 224, 288, 256, 256), 4133, "f32", 2),
+    ("stream_n2", 64, (32, 96), 4200, "f32", 2),
+    ("stream_n3", 96, (32, 64, 96), 4111, "bf16", 2),
+    ("stream_n4_top1", 128, (32, 224, 96, 160), 4500, "bf16", 1),
+    ("stream_n16", 128, (64,) * 16, 6001, "f32", 2),
+    ("stream_n24", 64, (32,) * 24, 1500, "bf16", 2),
+    ("stream_n64", 64, (32,) * 64, 3000, "f32", 2),
+    ("stream_n64_bf16", 96, (32,) * 64, 1025, "bf16", 2),
+    ("stream_ragged_d", 1120, (64, 192, 128, 128), 4100, "bf16", 2),
+    ("stream_many_groups", 32, (32,) * 8, 40000, "bf16", 2),
+    # more than 16 experts on a small batch, and an expert count that is not a power of two: the router that
+    # reads (a padded copy of) W_gate from memory
+    ("block_n24", 64, (32,) * 24, 300, "bf16", 2),
+    ("block_n40_f32", 96, (32,) * 40, 333, "f32", 2),
 ]
 
 
@@ -86,6 +103,26 @@ def test_route_with_bias_and_empty_expert():
     got = r.routing_host()
     check_routing(inp, got)
     assert got["counts"][2] == 0 and got["counts"][4] > 300
+
+
+@pytest.mark.parametrize("T", [50, 5000], ids=["token_router", "stream_router"])
+def test_route_masked_experts_second_pick_differs_from_first(T):
+    # every expert but one masked out by an infinite negative bias: the second pick is the lowest other index
+    # (as in a stable descending sort) with gate weight 0, never a repeat of the first
+    from oracle import modse_oracle as orc2
+    for keep in (0, 5):
+        bias = np.full(8, -np.inf, dtype=np.float32)
+        bias[keep] = 0.0
+        inp = make("masked", 128, (64,) * 8, T, "f32", bias=bias, seed=9 + keep)
+        r = _runner(inp)
+        r.route()
+        got = r.routing_host()
+        ref = orc2.route(inp.x, inp.W_gate, 8, 2, bias)
+        assert (got["topk_idx"] == ref.topk_idx).all()
+        assert (got["topk_idx"][:, 0] == keep).all() and (got["topk_idx"][:, 1] == (1 if keep == 0 else 0)).all()
+        assert (got["topk_w"] == np.array([1.0, 0.0], dtype=np.float32)).all()
+        counts, offsets, row_of, src_of = orc2.permutation_from_indices(got["topk_idx"], 8)
+        assert (got["counts"] == counts).all() and (got["row_of"] == row_of).all() and (got["src_of"] == src_of).all()
 
 
 def test_route_exact_ties_go_to_lower_index():

@@ -50,6 +50,16 @@ def test_workspace_size_grows_with_tokens_and_backward():
     assert m.modse_saved_size(256, C0["d_ff"], 2, "bf16", 512) > 0
 
 
+def test_forward_workspace_is_small_when_saved_carries_the_activations():
+    full, small = ws(16384, m.WS_FWD), ws(16384, m.WS_FWD_SAVED)
+    # without `saved` the workspace holds the permuted rows and the expert outputs: 2 * T * k * d elements at least
+    assert full - small >= 2 * 16384 * 2 * 256 * 4
+    assert 0 < small < 16384 * 64
+    assert ws(512, 3) == INVALID and ws(512, -1) == INVALID
+    # a layer whose expert count is not a power of two keeps a padded copy of the router matrices
+    assert ws(512, d_ff=[128] * 6) - ws(512, d_ff=[128] * 8) > 0
+
+
 @pytest.mark.parametrize("over,code", [
     (dict(d_model=250), INVALID),
     (dict(d_ff=[128, 100]), INVALID),
