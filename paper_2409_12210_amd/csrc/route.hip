@@ -165,23 +165,26 @@ struct GlobalRows {
   __device__ void fetch(int r, float (&wf)[EC]) const { load_row<EC>(W + (size_t)r * ldw + e0, wf); }
 };
 
-// The same from the LDS copy that router_stream_kernel keeps: floats, NE per row; the eight rows of one lane
-// and step lie together, followed by 16 bytes of padding, so that the 16 lanes which a 128-bit LDS read
-// serves together fall into different banks.
-constexpr int rs_group_bytes(int NE) { return 8 * NE * 4 + 16; }
-template <int NE, int EC>
+// The same from the LDS copy that router_stream_kernel keeps: elements of type W (double when the matrix
+// fits that way, else float), NE per row; the eight rows of one lane and step lie together, followed by 16
+// bytes of padding, so that the 16 lanes which a 128-bit LDS read serves together fall into different banks.
+constexpr int rs_group_bytes(int NE, int elem) { return 8 * NE * elem + 16; }
+template <typename W, int NE, int EC>
 struct LdsRows {
   const char* base;
   int e0;
-  __device__ void fetch(int r, float (&wf)[EC]) const {
-    const char* p = base + (r >> 3) * rs_group_bytes(NE) + (r & 7) * NE * 4 + e0 * 4;
-    if constexpr (EC >= 4) {
+  __device__ void fetch(int r, W (&wf)[EC]) const {
+    constexpr int PER = 16 / sizeof(W);  // elements per 128-bit read
+    typedef W vec_t __attribute__((ext_vector_type(PER)));
+    const char* p = base + (r >> 3) * rs_group_bytes(NE, sizeof(W)) + (r & 7) * NE * (int)sizeof(W) + e0 * (int)sizeof(W);
+    if constexpr (EC >= PER) {
 #pragma unroll
-      for (int e = 0; e < EC; e += 4) {
-        const f32x4 q = *reinterpret_cast<const f32x4*>(p + e * 4);
-        wf[e] = q.x; wf[e + 1] = q.y; wf[e + 2] = q.z; wf[e + 3] = q.w;
+      for (int e = 0; e < EC; e += PER) {
+        const vec_t q = *reinterpret_cast<const vec_t*>(p + e * sizeof(W));
+#pragma unroll
+        for (int j = 0; j < PER; ++j) wf[e + j] = q[j];
       }
-    } else {
+    } else {  // two floats
       const f32x2 q = *reinterpret_cast<const f32x2*>(p);
       wf[0] = q.x; wf[1] = q.y;
     }
@@ -243,7 +246,7 @@ __device__ inline void lane_dots(const T* const (&row)[TOK], int d, int lane, co
 template <int NE>
 struct RouterShape {
   static constexpr int EC = NE < 16 ? NE : 16;
-  static constexpr int TOK = 32 / EC < 8 ? 32 / EC : 8;
+  static constexpr int TOK = 32 / EC < 4 ? 32 / EC : 4;  // (more tokens: their row registers no longer fit)
   static constexpr int V = TOK * EC;
 };
 
@@ -339,26 +342,59 @@ __global__ __launch_bounds__(ROUTE_THREADS, 2) void router_kernel(const T* __res
 }
 
 // Router for large batches without the optional gate parts.  One 512-thread block per CU copies W_gate into LDS
-// once, as floats (exact for both input types), and then walks over groups of 64 tokens (two histogram blocks of
-// TPB tokens), eight tokens per wave: the matrix rows then cost an LDS read instead of a trip through the
-// vector memory pipeline per TOK tokens, which is what holds router_kernel back.  Sums are float64 FMAs in a
-// fixed order per lane, then wave_sum_values: results do not depend on timing.
+// once (as float64 when that fits RS_W_BYTES, else as float: both exact) and then walks over groups of 64 tokens
+// (two histogram blocks of TPB tokens), eight tokens per wave: the matrix rows then cost an LDS read instead of a
+// trip through the vector memory pipeline per TOK tokens, which is what holds router_kernel back.
+// A wave's work is a flat sequence of steps (group, pass of TOK tokens, chunk of EC expert columns, 512 columns
+// of the token rows); the loads of the step two ahead are issued before the arithmetic of the current step,
+// across pass and group boundaries, and the first two steps are under way while W_gate is being copied.
+// Sums are float64 FMAs in a fixed order per lane, then wave_sum_values: results do not depend on timing.
 constexpr int RS_THREADS = 512, RS_WAVES = RS_THREADS / 64, RS_TOKENS = 64;
 constexpr int RS_W_BYTES = 136 * 1024;
 
-template <typename T, int NE>
+template <typename T, int NE, typename W>
 __global__ __launch_bounds__(RS_THREADS) void router_stream_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
                                                                   const float* __restrict__ bias, int ntok, int d,
                                                                   int N, int top_k, int32_t* __restrict__ topk_idx,
                                                                   float* __restrict__ topk_w,
                                                                   int32_t* __restrict__ blockhist) {
-  constexpr int TOK = RouterShape<NE>::TOK, EC = RouterShape<NE>::EC;
-  constexpr int GB = rs_group_bytes(NE);
+  using S = RouterShape<NE>;
+  constexpr int TOK = S::TOK, EC = S::EC, V = S::V;
+  constexpr int NPASS = 8 / TOK, NCHUNK = NE / EC;
+  constexpr int GB = rs_group_bytes(NE, sizeof(W));
   constexpr int HW = MODSE_MAX_EXPERTS + 1;
   __shared__ __attribute__((aligned(16))) char s_w[RS_W_BYTES];
   __shared__ double s_logit[RS_WAVES][TOK][NE];
   __shared__ int s_hist[2 * HW];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ngroups = (ntok + RS_TOKENS - 1) / RS_TOKENS;
+  const int nhist = (ntok + TPB - 1) / TPB;
+  const int nstep = (d + 511) >> 9;
+
+  // the loader runs two steps ahead of the arithmetic
+  Raw8<T> cur[TOK], nx1[TOK], nx2[TOK];
+  int l_grp = blockIdx.x, l_pass = 0, l_chunk = 0, l_st = 0;
+  auto load_next = [&](Raw8<T> (&dst)[TOK]) {
+    if (l_grp < ngroups) {
+      const int tbase = l_grp * RS_TOKENS + wave * 8 + l_pass * TOK;
+      const int c = min(l_st * 512 + lane * 8, d - 8);
+#pragma unroll
+      for (int tt = 0; tt < TOK; ++tt)  // rows past the end repeat the last token; never written
+        dst[tt].load(x + (size_t)min(tbase + tt, ntok - 1) * d + c);
+    }
+    if (++l_st == nstep) {
+      l_st = 0;
+      if (++l_chunk == NCHUNK) {
+        l_chunk = 0;
+        if (++l_pass == NPASS) {
+          l_pass = 0;
+          l_grp += gridDim.x;
+        }
+      }
+    }
+  };
+  load_next(cur);
+  load_next(nx1);
 
   for (int r = tid; r < d; r += RS_THREADS) {  // W_gate -> LDS; columns past N read as zero
     float wf[NE];
@@ -368,23 +404,60 @@ __global__ __launch_bounds__(RS_THREADS) void router_stream_kernel(const T* __re
 #pragma unroll
       for (int e = 0; e < NE; ++e) wf[e] = e < N ? (float)Wg[(size_t)r * N + e] : 0.f;
     }
-    float* dst = reinterpret_cast<float*>(s_w + (r >> 3) * GB + (r & 7) * NE * 4);
+    W* dst = reinterpret_cast<W*>(s_w + (r >> 3) * GB + (r & 7) * NE * (int)sizeof(W));
 #pragma unroll
-    for (int e = 0; e < NE; ++e) dst[e] = wf[e];
+    for (int e = 0; e < NE; ++e) dst[e] = (W)wf[e];
   }
   if (tid < 2 * HW) s_hist[tid] = 0;
   __syncthreads();
 
-  const int ngroups = (ntok + RS_TOKENS - 1) / RS_TOKENS;
-  const int nhist = (ntok + TPB - 1) / TPB;
   for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
-    for (int pass = 0; pass < 8 / TOK; ++pass) {
+    for (int pass = 0; pass < NPASS; ++pass) {
       const int tbase = grp * RS_TOKENS + wave * 8 + pass * TOK;
-      const T* row[TOK];
+#pragma unroll 1
+      for (int e0 = 0; e0 < NE; e0 += EC) {
+        const LdsRows<W, NE, EC> rows = {s_w, e0};
+        double acc[V];
 #pragma unroll
-      for (int tt = 0; tt < TOK; ++tt)  // rows past the end repeat the last token; never written
-        row[tt] = x + (size_t)min(tbase + tt, ntok - 1) * d;
-      wave_logits<T, NE>(row, d, lane, [&](int e0) { return LdsRows<NE, EC>{s_w, e0}; }, s_logit[wave]);
+        for (int i = 0; i < V; ++i) acc[i] = 0.0;
+        for (int st = 0; st < nstep; ++st) {
+          load_next(nx2);
+          const int c = st * 512 + lane * 8;
+          if (c < d) {
+            W wf[EC];
+            rows.fetch(c, wf);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              W wn[EC];
+              if (i < 7) rows.fetch(c + i + 1, wn);  // the next matrix row is on its way during this row's arithmetic
+              double wd[EC];
+#pragma unroll
+              for (int e = 0; e < EC; ++e) wd[e] = (double)wf[e];
+#pragma unroll
+              for (int tt = 0; tt < TOK; ++tt) {
+                const double xd = (double)cur[tt].get(i);
+#pragma unroll
+                for (int e = 0; e < EC; ++e) acc[tt * EC + e] = fma(xd, wd[e], acc[tt * EC + e]);
+              }
+              if (i < 7) {
+#pragma unroll
+                for (int e = 0; e < EC; ++e) wf[e] = wn[e];
+              }
+              __builtin_amdgcn_sched_barrier(0);  // (see lane_dots)
+            }
+          }
+#pragma unroll
+          for (int tt = 0; tt < TOK; ++tt) {
+            cur[tt] = nx1[tt];
+            nx1[tt] = nx2[tt];
+          }
+        }
+        wave_sum_values<V>(acc, lane);
+        if (lane < V) {
+          const int v = bitrev<Log2<V>::value>(lane);
+          s_logit[wave][v / EC][e0 + v % EC] = acc[0];
+        }
+      }
       __syncthreads();
       if (lane < TOK && tbase + lane < ntok) {
         const int t = tbase + lane;
@@ -999,7 +1072,7 @@ enum RouterKind { ROUTER_TOKEN, ROUTER_STREAM, ROUTER_BLOCK };
 RouterKind router_kind(const LayerDims& L, const GateExtPtrs* G) {
   if (G) return ROUTER_BLOCK;
   if (L.N <= 16 && L.T <= ROUTER_TOKEN_MAX_T) return ROUTER_TOKEN;
-  if ((size_t)(L.d / 8) * rs_group_bytes(padded_experts(L.N)) <= (size_t)RS_W_BYTES && L.T >= 1024) return ROUTER_STREAM;
+  if ((size_t)(L.d / 8) * rs_group_bytes(padded_experts(L.N), 4) <= (size_t)RS_W_BYTES && L.T >= 1024) return ROUTER_STREAM;
   return ROUTER_BLOCK;
 }
 
@@ -1042,9 +1115,16 @@ hipError_t router_typed(const LayerDims& L, const void* xv, const void* Wgv, con
   } else if (kind == ROUTER_STREAM) {
     const int ngroups = (L.T + RS_TOKENS - 1) / RS_TOKENS;
     const dim3 grid(std::min(ngroups, 256)), blk(RS_THREADS);  // one block per CU holds the LDS copy of W_gate
-#define MODSE_LAUNCH_STREAM_ROUTER(NE_)                                                                          \
-  hipLaunchKernelGGL((router_stream_kernel<T, NE_>), grid, blk, 0, s, x, Wg, bias, L.T, L.d, L.N, L.k, R.topk_idx, \
-                     R.topk_w, B.blockhist)
+    const bool w64 = (size_t)(L.d / 8) * rs_group_bytes(NE, 8) <= (size_t)RS_W_BYTES;  // W_gate fits as float64
+#define MODSE_LAUNCH_STREAM_ROUTER(NE_)                                                                            \
+  do {                                                                                                            \
+    if (w64)                                                                                                      \
+      hipLaunchKernelGGL((router_stream_kernel<T, NE_, double>), grid, blk, 0, s, x, Wg, bias, L.T, L.d, L.N, L.k, \
+                         R.topk_idx, R.topk_w, B.blockhist);                                                      \
+    else                                                                                                          \
+      hipLaunchKernelGGL((router_stream_kernel<T, NE_, float>), grid, blk, 0, s, x, Wg, bias, L.T, L.d, L.N, L.k,  \
+                         R.topk_idx, R.topk_w, B.blockhist);                                                      \
+  } while (0)
     switch (NE) {
       case 2: MODSE_LAUNCH_STREAM_ROUTER(2); break;
       case 4: MODSE_LAUNCH_STREAM_ROUTER(4); break;
