@@ -391,8 +391,6 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   void* Xp = saved ? static_cast<char*>(saved) + saved_layout(L, dt).Xp : wsb + w.Xp;
   HIP_TRY(launch_router(L, dt, x, W_gate, logit_bias, R, RB, ext ? &G : nullptr, s));
   stamp.mark(MODSE_STAGE_ROUTE);
-  HIP_TRY(launch_permute(L, dt, x, R, RB, Xp, ext ? &G : nullptr, s));
-  stamp.mark(MODSE_STAGE_PERMUTE);
 
   FwdPlanArgs pa;
   std::memset(&pa, 0, sizeof(pa));
@@ -412,8 +410,14 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   const int kchunk = saved ? 0 : splitk_chunk(L);
   pa.kchunk = kchunk;
   pa.Opart = reinterpret_cast<float*>(wsb + w.Opart);
-  HIP_TRY(launch_plan_fwd(L, dt, R.counts, R.offsets, pa, s));
-  stamp.mark(MODSE_STAGE_PLAN);
+  // histogram, scan, stable scatter, then the tile plans (one launch for all of it on decode-sized batches,
+  // which then shows under MODSE_STAGE_PERMUTE alone)
+  HIP_TRY(launch_permute(L, dt, x, R, RB, Xp, ext ? &G : nullptr, T <= MODSE_PERMUTE_SMALL_MAX_T ? &pa : nullptr, s));
+  stamp.mark(MODSE_STAGE_PERMUTE);
+  if (T > MODSE_PERMUTE_SMALL_MAX_T) {
+    HIP_TRY(launch_plan_fwd(L, dt, R.counts, R.offsets, pa, s));
+    stamp.mark(MODSE_STAGE_PLAN);
+  }
 
   const int skinny = T <= MODSE_SKINNY_TOKENS;
   HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU, pa.up, 0, saved != nullptr, tiles_bound(L, T, pa.up_tile, true), s, -1,

@@ -8,6 +8,7 @@
 #define MODSE_MAX_EXPERTS 64
 #define MODSE_MAX_PROBLEMS (3 * MODSE_MAX_EXPERTS)  // the three weight-gradient GEMMs share one launch
 #define MODSE_SKINNY_TOKENS 64           // batches up to this size take the decode-shaped forward GEMMs
+#define MODSE_PERMUTE_SMALL_MAX_T 64      // batches up to this size take the fused permute + plan launch
 #define MODSE_ROUTE_TOKENS_PER_BLOCK 32  // tokens handled by one block of the router / scatter kernels
 
 typedef __bf16 bf16_t;
@@ -156,8 +157,11 @@ inline size_t route_wpad_bytes(const LayerDims& L, size_t elem_size) {
 // be null).
 hipError_t launch_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
                          const RoutingPtrs& R, const RouteBufs& B, const GateExtPtrs* G, hipStream_t s);
+struct FwdPlanArgs;
+// plan != null: also makes the tile plans of the two forward GEMMs (batches of at most
+// MODSE_PERMUTE_SMALL_MAX_T tokens do all of this in one launch)
 hipError_t launch_permute(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, const RouteBufs& B,
-                          void* Xp, const GateExtPtrs* G, hipStream_t s);
+                          void* Xp, const GateExtPtrs* G, const FwdPlanArgs* plan, hipStream_t s);
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
                         const RoutingPtrs& R, const RouteBufs& B, void* Xp, const GateExtPtrs* G, hipStream_t s);
 hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,

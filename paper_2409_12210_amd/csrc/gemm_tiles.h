@@ -4,9 +4,6 @@
 
 namespace modse_gemm {
 
-#ifndef MAGIC_ONLY
-#define MAGIC_ONLY 0
-#endif
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;  // tiles of GROUP_M consecutive row blocks are walked column-first (L2 reuse)
 
@@ -22,7 +19,7 @@ __host__ __device__ inline uint32_t tile_magic(uint32_t d, uint64_t n_max) {
   return (uint32_t)(((1ull << 32) + d - 1) / d);
 }
 __device__ inline uint32_t magic_div(uint32_t n, uint32_t d, uint32_t magic) {
-  return MAGIC_ONLY ? __umulhi(n, magic) : (magic ? __umulhi(n, magic) : n / d);
+  return magic ? __umulhi(n, magic) : n / d;
 }
 
 // Tile `local` of a problem with mtiles x ntiles tiles: tiles are walked in groups of GROUP_M row blocks,

@@ -8,6 +8,7 @@
 #include <climits>
 
 #include "common.h"
+#include "gemm_plan.h"
 
 namespace {
 
@@ -772,6 +773,95 @@ __global__ __launch_bounds__(ROUTE_THREADS) void scatter_kernel(const T* __restr
   }
 }
 
+// Decode-sized batches (at most 64 tokens): histogram, offsets, stable scatter and, when a forward pass follows,
+// the tile plans of its two GEMMs in ONE launch instead of four; at this size every launch gap shows in the
+// layer time.  One block per token.  Wave 0 of every block holds one token per lane and ranks all of them with
+// one ballot per expert (the same rows as scatter_kernel: tokens of an expert in token order); block 0 also
+// writes the routing outputs and the plans; block t copies token t's row to its permuted places.
+// Near-tie total: from near_flag (one-block-per-token router) or, when that is null, from the last column of
+// the router's block histograms.
+template <typename T>
+__global__ __launch_bounds__(256) void permute_small_kernel(const T* __restrict__ x, int ntok, int d, int N, int top_k,
+                                                            const int32_t* __restrict__ topk_idx,
+                                                            const int32_t* __restrict__ near_flag,
+                                                            const int32_t* __restrict__ blockhist, RoutingPtrs R,
+                                                            T* __restrict__ Xp, LayerDims L, int esize,
+                                                            FwdPlanArgs plan, int with_plan) {
+  __shared__ int s_row[64][2];
+  __shared__ int s_counts[MODSE_MAX_EXPERTS], s_offsets[MODSE_MAX_EXPERTS + 1];
+  __shared__ int s_tiles[MODSE_MAX_PROBLEMS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool first = blockIdx.x == 0;
+  if (wave == 0) {
+    const int t = lane;
+    const bool valid = t < ntok;
+    int e0 = -1, e1 = -1;
+    if (valid) {
+      e0 = topk_idx[(size_t)t * top_k];
+      if (top_k == 2) e1 = topk_idx[(size_t)t * top_k + 1];
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int run = 0, row0 = 0, row1 = 0, my_count = 0, my_offset = 0;
+    for (int e = 0; e < N; ++e) {
+      const unsigned long long m = __ballot(e0 == e || e1 == e);
+      const int rank = __popcll(m & below), c = __popcll(m);
+      if (e0 == e) row0 = run + rank;
+      if (e1 == e) row1 = run + rank;
+      if (lane == e) {
+        my_count = c;
+        my_offset = run;
+      }
+      run += c;
+    }
+    if (lane < N) {
+      s_counts[lane] = my_count;
+      s_offsets[lane] = my_offset;
+    }
+    if (lane == 0) s_offsets[N] = run;
+    if (valid) {
+      s_row[t][0] = row0;
+      s_row[t][1] = row1;
+    }
+    if (first) {
+      int near;
+      if (near_flag) {
+        near = __popcll(__ballot(valid && near_flag[t] != 0));
+      } else {
+        near = 0;
+        for (int b = 0; b * TPB < ntok; ++b) near += blockhist[(size_t)b * (N + 1) + N];
+      }
+      if (lane < N) {
+        R.counts[lane] = my_count;
+        R.offsets[lane] = my_offset;
+      }
+      if (lane == 0) {
+        R.offsets[N] = run;
+        R.near_tie_count[0] = near;
+      }
+      if (valid) {
+        R.row_of[(size_t)t * top_k] = row0;
+        R.src_of[row0] = t * top_k;
+        if (top_k == 2) {
+          R.row_of[(size_t)t * top_k + 1] = row1;
+          R.src_of[row1] = t * top_k + 1;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (first && with_plan) modse_gemm::plan_fwd_body(L, esize, s_counts, s_offsets, plan, s_tiles);
+  if (Xp == nullptr) return;
+  const int t = blockIdx.x;
+  const int row0 = s_row[t][0];
+  const int row1 = top_k == 2 ? s_row[t][1] : -1;
+  constexpr int VEC = 16 / sizeof(T);
+  for (int c = tid * VEC; c < d; c += 256 * VEC) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(x + (size_t)t * d + c);
+    *reinterpret_cast<f32x4*>(Xp + (size_t)row0 * d + c) = v;
+    if (row1 >= 0) *reinterpret_cast<f32x4*>(Xp + (size_t)row1 * d + c) = v;
+  }
+}
+
 // y[t] = sum_j g[t,j] * O[row_of[t,j]]   (Eq. 1 on permuted expert outputs; one wave per token, fp32 math)
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ O, int ntok, int d, int top_k,
@@ -1155,14 +1245,22 @@ hipError_t router_typed(const LayerDims& L, const void* xv, const void* Wgv, con
   return e;
 }
 
-// histogram (where the router has not made it), scan over blocks, stable scatter
+// histogram (where the router has not made it), scan over blocks, stable scatter; batches of at most
+// PERMUTE_SMALL_MAX_T tokens: one fused launch, which also makes the forward tile plans when `plan` is given
 template <typename T>
-hipError_t permute_typed(const LayerDims& L, const void* xv, const RoutingPtrs& R, const RouteBufs& B, void* Xpv,
-                         const GateExtPtrs* G, hipStream_t s) {
+hipError_t permute_typed(const LayerDims& L, modse_dtype dt, const void* xv, const RoutingPtrs& R, const RouteBufs& B,
+                         void* Xpv, const GateExtPtrs* G, const FwdPlanArgs* plan, hipStream_t s) {
   const T* x = static_cast<const T*>(xv);
   const int nb = (L.T + TPB - 1) / TPB;
   hipError_t e;
-  if (router_kind(L, G) == ROUTER_TOKEN) {
+  const bool token_router = router_kind(L, G) == ROUTER_TOKEN;
+  if (L.T <= MODSE_PERMUTE_SMALL_MAX_T) {
+    hipLaunchKernelGGL((permute_small_kernel<T>), dim3(L.T), dim3(256), 0, s, x, L.T, L.d, L.N, L.k, R.topk_idx,
+                       token_router ? B.near_flag : nullptr, B.blockhist, R, static_cast<T*>(Xpv), L,
+                       dt == MODSE_F32 ? 4 : 2, plan ? *plan : FwdPlanArgs{}, plan ? 1 : 0);
+    return hipGetLastError();
+  }
+  if (token_router) {
     hipLaunchKernelGGL(route_hist_kernel, dim3(nb), dim3(64), 0, s, R.topk_idx, B.near_flag, L.T, L.N, L.k,
                        B.blockhist);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1172,7 +1270,9 @@ hipError_t permute_typed(const LayerDims& L, const void* xv, const RoutingPtrs& 
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((scatter_kernel<T>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, L.T, L.d, L.N, L.k, R.topk_idx,
                      R.offsets, B.blockhist, R.row_of, R.src_of, static_cast<T*>(Xpv));
-  return hipGetLastError();
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (plan) e = launch_plan_fwd(L, dt, R.counts, R.offsets, *plan, s);
+  return e;
 }
 
 // dX and the gradient of one router-side matrix, 8 expert columns per launch
@@ -1202,14 +1302,15 @@ hipError_t launch_router(const LayerDims& L, modse_dtype dt, const void* x, cons
 }
 
 hipError_t launch_permute(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, const RouteBufs& B,
-                          void* Xp, const GateExtPtrs* G, hipStream_t s) {
-  return dt == MODSE_F32 ? permute_typed<float>(L, x, R, B, Xp, G, s) : permute_typed<bf16_t>(L, x, R, B, Xp, G, s);
+                          void* Xp, const GateExtPtrs* G, const FwdPlanArgs* plan, hipStream_t s) {
+  return dt == MODSE_F32 ? permute_typed<float>(L, dt, x, R, B, Xp, G, plan, s)
+                         : permute_typed<bf16_t>(L, dt, x, R, B, Xp, G, plan, s);
 }
 
 hipError_t launch_route(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
                         const RoutingPtrs& R, const RouteBufs& B, void* Xp, const GateExtPtrs* G, hipStream_t s) {
   const hipError_t e = launch_router(L, dt, x, W_gate, bias, R, B, G, s);
-  return e != hipSuccess ? e : launch_permute(L, dt, x, R, B, Xp, G, s);
+  return e != hipSuccess ? e : launch_permute(L, dt, x, R, B, Xp, G, nullptr, s);
 }
 
 hipError_t launch_routing_stats(const LayerDims& L, const int32_t* topk_idx, int32_t* slot_counts, float* summary,

@@ -46,8 +46,9 @@ CASES = [
     ("n64_f32", 64, (32,) * 64, 203, "f32", 2),
     ("n64_bf16", 96, (32,) * 64, 333, "bf16", 2),
     ("n40_bf16", 64, (32,) * 40, 97, "bf16", 2),
+    ("decode_n8", 256, (128, 384, 192, 320, 224, 288, 256, 256), 40, "bf16", 2),
 ]
-LAYER_CASES = CASES[:4] + CASES[5:8]
+LAYER_CASES = CASES[:4] + CASES[5:8] + CASES[-1:]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])

@@ -66,6 +66,8 @@ ROUTE_CASES = [
     ("decode_n3", 96, (32, 64, 96), 64, "bf16", 2),
     ("decode_top1", 256, (128, 384, 192, 320), 33, "bf16", 1),
     ("decode_wide", 4096, (64, 192, 128, 128, 64, 192, 128, 128), 64, "bf16", 2),
+    ("decode_n24", 64, (32,) * 24, 50, "bf16", 2),      # block router + the fused decode-sized permute
+    ("decode_n64_top1", 64, (32,) * 64, 64, "f32", 1),
     # batches beyond 4096 tokens (or with more than 16 experts, from 1024 tokens) take the router that keeps
     # W_gate in LDS: every padded expert count, both dtypes, ragged token counts, several groups per block
     ("stream_n8", 256, (128, 384, 192, 320, 224, 288, 256, 256), 5000, "bf16", 2),
