@@ -389,8 +389,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   f32x16 acc[NB][MI][NI];
   // The 16 MFMAs of one K half; in their shadow this wave's four loads of cursor c's panel (into ring slot
   // `slot`), one after every fourth MFMA.
-  auto mfma_half = [&](LoadCursor& c, uint32_t (&off)[UPW], uint32_t dst) {
-    const int fast = c.fast;
+  auto mfma_half = [&](LoadCursor& c, uint32_t (&off)[UPW], uint32_t dst, auto always) {
+    const int fast = decltype(always)::value ? 1 : c.fast;
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int t = 0; t < 2 * NB * MI * NI; ++t) {
@@ -430,6 +430,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     __builtin_amdgcn_sched_barrier(0);
   };
   auto slot_add = [&](int s, int d) { return (s + d) >= NSLOT ? s + d - NSLOT : s + d; };
+  // how many times a cursor can move on and still stand on a full step of the same tile and pass
+  auto fast_left = [&](const LoadCursor& c) -> int {
+    if (!c.fast) return 0;
+    const int full = c.K / BK;
+    const int lim = (EPI == EPI_STORE_DUALK && c.step >= c.nk) ? c.nk + full : full;
+    return lim - c.step - 1;
+  };
 
   if (any_step) {
     wait_panels(0);
@@ -450,8 +457,46 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
   };
   zero_acc();
   while (cc.w.valid) {
+    int s = 0;
 #pragma unroll 1
-    for (int s = 0; s < cc.nsteps; ++s) {
+    while (s < cc.nsteps) {
+      // Steady stretch: the steps during which both load cursors stay on full steps of their present tile and
+      // pass.  Nothing about a cursor has to be decided then: its source moves on by one step, four loads go
+      // out in every MFMA phase, and four loads (the youngest) may stay in flight at either wait, for both
+      // wave groups alike.
+      {
+        const int n0 = fast_left(c0), n1 = fast_left(c1);
+        int n = n0 < n1 ? n0 : n1;
+        n = n < cc.nsteps - s ? n : cc.nsteps - s;
+        s += n;
+#pragma unroll 1
+        for (; n > 0; --n) {
+          const char* abuf = ring + sa * PANEL;
+          const char* bbuf = ring + slot_add(sa, 1) * PANEL;
+          load_frags(abuf, bbuf, 0, 0);
+          load_frags(abuf, bbuf, 1, 1);
+          __builtin_amdgcn_sched_barrier(0);
+          c1.src += c1.kbytes;
+          ++c1.step;
+          const uint32_t dst0 = panel_dst(slot_add(sa, d0)), dst1 = panel_dst(slot_add(sa, d1));
+          phase_end();
+          mfma_half(c0, off0, dst0, std::true_type{});
+          phase_end();
+          load_frags(abuf, bbuf, 2, 0);
+          load_frags(abuf, bbuf, 3, 1);
+          __builtin_amdgcn_sched_barrier(0);
+          c0.src += c0.kbytes;
+          ++c0.step;
+          wait_panels(1);
+          phase_end();
+          mfma_half(c1, off1, dst1, std::true_type{});
+          wait_panels(1);
+          phase_end();
+          sa = slot_add(sa, 2);
+        }
+        if (s >= cc.nsteps) break;
+      }
+      ++s;
       const char* abuf = ring + sa * PANEL;
       const char* bbuf = ring + slot_add(sa, 1) * PANEL;
       load_frags(abuf, bbuf, 0, 0);
@@ -461,7 +506,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       const uint32_t dst0 = panel_dst(slot_add(sa, d0)), dst1 = panel_dst(slot_add(sa, d1));
       if (grp_y) a_ahead = c0.w.valid;
       phase_end();
-      mfma_half(c0, off0, dst0);
+      mfma_half(c0, off0, dst0, std::false_type{});
       phase_end();
       load_frags(abuf, bbuf, 2, 0);
       load_frags(abuf, bbuf, 3, 1);
@@ -471,7 +516,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       // at the end of this phase of the late waves the panels of the next step must be complete
       if (grp_y) wait_panels(a_ahead);
       phase_end();
-      mfma_half(c1, off1, dst1);
+      mfma_half(c1, off1, dst1, std::false_type{});
       if (!grp_y) wait_panels(a_ahead);
       phase_end();
       sa = slot_add(sa, 2);

@@ -1,5 +1,7 @@
 // Helpers shared by the bf16 grouped GEMM kernels (gfx950): direct global->LDS loads, 16-byte global accesses.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_tiles.h"
 
