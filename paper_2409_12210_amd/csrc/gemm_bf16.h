@@ -534,9 +534,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       // 32 x 32 block (4 KiB) at a time: written in accumulator order (16 bytes per lane), read back row-wise,
       // so that global memory sees whole 128-byte lines.  The slots are this wave's own load units in the
       // two panels of the step just finished.
-      constexpr bool kStagedF32 = false;  // (switched off: the staged path does not reproduce the direct one yet)
       const bool interior = cc.w.m0 + BM <= cM && cc.w.n0 + BN <= cN;
-      if (kStagedF32 && interior && !accumulate && cc.nsteps != 0) {
+      if (interior && !accumulate && cc.nsteps != 0) {
         char* const fslot[2] = {grp_y ? ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024
                                       : ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024,
                                 ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024};
@@ -651,21 +650,39 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       const bool interior = cc.w.m0 + BM <= cM && cc.w.n0 + BN <= cN;
       const uint32_t voff = (uint32_t)(rrow * cld + rchunk * 8) * 2u;
       const char* const wave_c = cc.C + ((size_t)(cc.w.m0 + wm * WM) * cld + cc.w.n0 + wn * WN) * 2;
-      if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
+      // rows of a staged unit to global memory, for a tile inside the matrix: scalar address of the unit's row
+      // group + this lane's fixed offset; no masks, no per-lane 64-bit arithmetic, one basic block
+      auto store_unit_interior = [&](char* slot, int u, const char* wave_base) {
+        const char* ub = wave_base + ((size_t)(u / NJP) * 32 * cld + (u % NJP) * 64) * 2;
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-          if (unit_m(u) >= cM) continue;
-          char* slot = (u & 1) ? slot1 : slot0;
-          put_unit(slot, acc[0][u / NJP][2 * (u % NJP)], acc[0][u / NJP][2 * (u % NJP) + 1]);
-          store_unit(slot, u, cc.C);
+        for (int it = 0; it < 4; ++it) {
+          const bf16x8 v = *row_pos(slot, it);
+          global_store16_s(ub + (size_t)it * 8 * cld * 2, voff, v);
+        }
+      };
+      const size_t wave_off = ((size_t)(cc.w.m0 + wm * WM) * cld + cc.w.n0 + wn * WN) * 2;
+      if constexpr (EPI == EPI_STORE || EPI == EPI_STORE_DUALK) {
+        if (interior) {
+#pragma unroll
+          for (int u = 0; u < NU; ++u) {
+            char* slot = (u & 1) ? slot1 : slot0;
+            put_unit(slot, acc[0][u / NJP][2 * (u % NJP)], acc[0][u / NJP][2 * (u % NJP) + 1]);
+            store_unit_interior(slot, u, wave_c);
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < NU; ++u) {
+            if (unit_m(u) >= cM) continue;
+            char* slot = (u & 1) ? slot1 : slot0;
+            put_unit(slot, acc[0][u / NJP][2 * (u % NJP)], acc[0][u / NJP][2 * (u % NJP) + 1]);
+            store_unit(slot, u, cc.C);
+          }
         }
       } else if constexpr (EPI == EPI_SWIGLU) {
-#pragma unroll
-        for (int u = 0; u < NU; ++u) {
-          if (unit_m(u) >= cM) continue;
+        // h = silu(a) b and the saved term p = dh/da go to the slots four columns at a time; q = dh/db
+        // takes b's place in the accumulator and follows once the slot of h is free
+        auto swiglu_unit = [&](int u) {
           const int i = u / NJP, j0 = 2 * (u % NJP);
-          // h = silu(a) b and the saved term p = dh/da go to the slots four columns at a time; q = dh/db
-          // takes b's place in the accumulator and follows once the slot of h is free
 #pragma unroll
           for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
@@ -683,11 +700,31 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
               *acc_pos(slot0, jj, r) = hv;
               if (save_pre) *acc_pos(slot1, jj, r) = pv;
             }
-          store_unit(slot0, u, cc.C);
-          if (save_pre) {
-            store_unit(slot1, u, cc.C2);
-            put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
-            store_unit(slot0, u, cc.C3);
+        };
+        if (interior) {
+#pragma unroll
+          for (int u = 0; u < NU; ++u) {
+            const int i = u / NJP, j0 = 2 * (u % NJP);
+            swiglu_unit(u);
+            store_unit_interior(slot0, u, cc.C + wave_off);
+            if (save_pre) {
+              store_unit_interior(slot1, u, cc.C2 + wave_off);
+              put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
+              store_unit_interior(slot0, u, cc.C3 + wave_off);
+            }
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < NU; ++u) {
+            if (unit_m(u) >= cM) continue;
+            const int i = u / NJP, j0 = 2 * (u % NJP);
+            swiglu_unit(u);
+            store_unit(slot0, u, cc.C);
+            if (save_pre) {
+              store_unit(slot1, u, cc.C2);
+              put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
+              store_unit(slot0, u, cc.C3);
+            }
           }
         }
       } else if constexpr (EPI == EPI_SWIGLU_BWD) {

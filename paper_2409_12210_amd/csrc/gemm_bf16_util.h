@@ -35,15 +35,17 @@ __device__ __forceinline__ void dma_b128_s(const void* base, uint32_t voff, uint
 typedef __attribute__((address_space(1))) bf16x8 global_bf16x8;
 __device__ __forceinline__ void global_store16(bf16_t* p, bf16x8 v) { *(global_bf16x8*)(uintptr_t)p = v; }
 __device__ __forceinline__ bf16x8 global_load16(const bf16_t* p) { return *(const global_bf16x8*)(uintptr_t)p; }
-// 16 bytes per lane to / from wave-uniform base + per-lane unsigned 32-bit byte offset.  The load is issued
+// 16 bytes per lane to / from wave-uniform base + per-lane unsigned 32-bit byte offset.  (The two wait states
+// behind a store: a store of more than 64 bits must not be followed at once by a VALU write of its data
+// registers, and the compiler's hazard handling does not look inside assembly.)  The load is issued
 // from assembly so that its wait can be written by hand: the compiler waits for every outstanding memory
 // operation as soon as loads and stores are mixed.  wait_loaded makes the values usable once at most
 // `younger` vector-memory loads issued after them are still in flight (loads complete in order).
 __device__ __forceinline__ void global_store16_s(const void* base, uint32_t voff, bf16x8 v) {
-  asm volatile("global_store_dwordx4 %0, %1, %2" ::"v"(voff), "v"(v), "s"(base) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(voff), "v"(v), "s"(base) : "memory");
 }
 __device__ __forceinline__ void global_store16_s(const void* base, uint32_t voff, f32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, %2" ::"v"(voff), "v"(v), "s"(base) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" ::"v"(voff), "v"(v), "s"(base) : "memory");
 }
 __device__ __forceinline__ bf16x8 global_load16_s(const void* base, uint32_t voff) {
   bf16x8 v;
