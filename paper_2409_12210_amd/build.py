@@ -108,7 +108,7 @@ def build(extra_flags=(), verbose: bool = True) -> str:
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
-        print(f"built {LIB} ({len(res)} kernels, none with scratch or accumulation registers)")
+        print(f"built {LIB} ({len(res)} kernels within the register budget)")
     return LIB
 
 

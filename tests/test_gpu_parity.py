@@ -152,6 +152,9 @@ FWD_CASES = [
     ("bf16_decode_17", 320, (32, 608, 288, 352), 17, "bf16", 2),
     ("bf16_decode_long_k", 256, (2080, 64, 1056, 992), 30, "bf16", 2),
     ("f32_decode", 256, (128, 384, 192, 320, 224, 288, 256, 256), 48, "f32", 2),
+    # d_model that is not a multiple of 64 (a K tail in the decode kernel)
+    ("bf16_decode_d96", 96, (32, 608, 288, 352), 20, "bf16", 2),
+    ("bf16_decode_64_tokens_one_expert", 128, (160, 96), 64, "bf16", 1),
 ]
 
 
