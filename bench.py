@@ -150,6 +150,28 @@ class Run:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps * 1e3
 
+    def timed_graph(self, steps, warmup):
+        """the same step captured once into a HIP graph and replayed (what a serving loop does with a
+        launch-bound step): ms per replay"""
+        import torch
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            self.step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                self.step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
     def stages(self, steps):
         """per-stage durations from HIP events that the library records on the launch stream"""
         import paper_2409_12210_amd as m
@@ -333,8 +355,11 @@ def main():
         c3 = Run("C3", "fwd")
         c3_ms = c3.timed(4 * k, 5)
         c3_st = c3.stages(4 * k)
+        c3_graph_ms = c3.timed_graph(4 * k, 5)
         wbytes = 3.0 * c3.cfg.d_model * sum(c3.cfg.d_ff) * 2
         out["c3_fwd"] = {"workload": "C3 forward (decode-shaped), T=64", "ms_per_step": round(c3_ms, 4),
+                         "ms_per_step_hip_graph": round(c3_graph_ms, 4),
+                         "whole_layer_gbs_hip_graph": round(wbytes / (c3_graph_ms * 1e-3) / 1e9, 1),
                          "stages_ms": {s: round(v, 4) for s, v in c3_st.items() if v > 0},
                          "weight_bytes": wbytes,
                          "gemm_stages_gbs": round(wbytes / ((c3_st["up"] + c3_st["down"]) * 1e-3) / 1e9, 1),
