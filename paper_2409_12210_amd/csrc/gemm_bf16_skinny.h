@@ -116,6 +116,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
   StepCursor ic;
   const char* ibase[2] = {nullptr, nullptr};  // operand this wave loads from, per pass of a dual-K product
   const char* ibase_a = nullptr;              // skinny tiles: the A operand (unit 0 of every wave)
+  bool ia_needed = true;                      // ... and whether any of its 8 rows exists (rows >= M are never stored)
   int ikstride = 1;                           // elements between consecutive K of that operand
   uint32_t ioff[UPW];  // byte offset of this lane's chunk per load unit (K offset 0) from the operand base
   // tiles without K steps (an expert that received no token, in a weight-gradient GEMM) take no stage
@@ -141,6 +142,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
       }
     }
     const int PM = P->M, PN = P->N, lda = P->lda, ldb = P->ldb;
+    if (SKINNY) ia_needed = __builtin_amdgcn_readfirstlane(ic.m0 + wave * 8 < PM ? 1 : 0) != 0;
     ikstride = loads_t ? (loads_a ? lda : ldb) : 1;
     if (loads_t) {  // unit = K rows 2u, 2u+1; LDS position (k, p) holds 16-byte chunk p ^ (4 * (k & 3))
 #pragma unroll
@@ -174,8 +176,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
     const char* base = ibase[pass] + (size_t)k0 * ikstride * 2;
     if (k0 + BK <= ic.K) {
 #pragma unroll
-      for (int i = first; i < first + count; ++i)
-        dma_b128_s((SKINNY && i == 0) ? ibase_a + (size_t)k0 * 2 : base, ioff[i], dst + unit_of(i) * 1024);
+      for (int i = first; i < first + count; ++i) {
+        if (SKINNY && i == 0) {  // the activation rows: every tile of the expert reads them again
+          if (ia_needed) dma_b128_s(ibase_a + (size_t)k0 * 2, ioff[i], dst + unit_of(i) * 1024);
+        } else  // a skinny tile's weights are read once in the whole launch
+          dma_b128_s<SKINNY>(base, ioff[i], dst + unit_of(i) * 1024);
+      }
     } else if (loads_t) {  // partial last step: K rows beyond K read zeros
 #pragma unroll
       for (int i = first; i < first + count; ++i) {
@@ -187,6 +193,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
     } else {  // last step of a pass when K % 64 != 0: chunks beyond K read zeros
 #pragma unroll
       for (int i = first; i < first + count; ++i) {
+        if (SKINNY && i == 0 && !ia_needed) continue;
         const char* src = ((SKINNY && i == 0) ? ibase_a + (size_t)k0 * 2 : base) + ioff[i];
         if (k0 + ((unit_of(i) & 1) ? lchunk_odd : lchunk_even) >= ic.K) src = reinterpret_cast<const char*>(g_zero_chunk);
         dma_b128(src, dst + unit_of(i) * 1024);
@@ -215,6 +222,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
   const bool any_stage = ic.valid;
   issue_slice(0, 0, UPW);  // stage of global step 0
   advance_issue();
+  // A skinny tile is bound by the weight stream, not by the matrix pipe: its stage loads go out in one piece as
+  // early as their buffer is free, straight behind the barrier that retires it (and those of step 1 right here),
+  // instead of in slices between the MFMA groups.  (A loader alone in this shape, 64 KiB stages, streams 6.7 TB/s.)
+  bool early_next = false;  // SKINNY: the stage of the step after the current one exists (and has been issued)
+  if constexpr (SKINNY) {
+    early_next = ic.valid;
+    issue_slice(1, 0, UPW);
+    advance_issue();
+  }
 
   // Fragments are double-buffered in registers: set (kk & 1) feeds the MFMAs of K slice kk while the
   // other set is being read from LDS.
@@ -302,11 +318,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
     for (int s = 0; s < cc.nsteps; ++s, ++g) {
       const char* buf = stages + (g & 1) * STAGE;
       const int nbuf = (g + 1) & 1;
-      const bool next_stage = ic.valid;  // a stage g+1 exists (maybe in the next tile); uniform in the workgroup
+      // a stage g+1 exists (maybe in the next tile); uniform in the workgroup
+      const bool next_stage = SKINNY ? early_next : ic.valid;
 #pragma unroll
       for (int kk = 0; kk < 3; ++kk) {
         load_frags(buf, kk + 1, (kk + 1) & 1);
-        if (kk < MODSE_DMA_SPREAD) {  // the loads of stage g+1 go out in slices between the MFMA groups
+        if (!SKINNY && kk < MODSE_DMA_SPREAD) {  // the loads of stage g+1 go out in slices between the MFMA groups
           __builtin_amdgcn_sched_barrier(0);
           issue_slice(nbuf, kk == 0 ? 0 : SLICE0, kk == 0 ? SLICE0 : UPW - SLICE0);
           __builtin_amdgcn_sched_barrier(0);
@@ -314,9 +331,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_skinny_kernel(c
         mfma_block(kk & 1);
       }
       __builtin_amdgcn_sched_barrier(0);
-      advance_issue();
+      if constexpr (!SKINNY) advance_issue();
       // (after the very last step the barrier only retires the buffer: the epilogue stages through it)
       stage_barrier();
+      if constexpr (SKINNY) {  // stage g+2 into the buffer of stage g, whose last fragments are in registers
+        early_next = ic.valid;
+        issue_slice(g & 1, 0, UPW);
+        advance_issue();
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (next_stage) load_frags(stages + nbuf * STAGE, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       mfma_block(1);

@@ -24,12 +24,20 @@ __device__ __forceinline__ void dma_b128(const void* gptr, uint32_t lds_base) {
                "v"(gptr)
                : "memory");
 }
-// same, address = wave-uniform base + per-lane unsigned 32-bit byte offset
+// same, address = wave-uniform base + per-lane unsigned 32-bit byte offset.  STREAM marks data that is read once
+// (the non-temporal hint): a plain read stream of 1.9 GB runs at 6.3 TB/s on this chip, a hinted one at 7.2 TB/s.
+template <bool STREAM = false>
 __device__ __forceinline__ void dma_b128_s(const void* base, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(
-                   __builtin_amdgcn_readfirstlane(lds_base)),
-               "v"(voff), "s"(uniform_ptr(base))
-               : "memory");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(
+                     __builtin_amdgcn_readfirstlane(lds_base)),
+                 "v"(voff), "s"(uniform_ptr(base))
+                 : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(
+                     __builtin_amdgcn_readfirstlane(lds_base)),
+                 "v"(voff), "s"(uniform_ptr(base))
+                 : "memory");
 }
 // 16-byte accesses through the global address space (a generic pointer would make them flat accesses)
 typedef __attribute__((address_space(1))) bf16x8 global_bf16x8;
