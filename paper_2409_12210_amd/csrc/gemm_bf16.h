@@ -523,6 +523,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
     }
 
     // ---- epilogue.  For register group r of block (i, j) the lane holds columns n .. n+3 of row m.
+    // The early waves wait here for the late waves' last MFMA phase, and the late waves wait behind their
+    // epilogue for the early waves' first phase of the next tile: both groups then run their epilogues at the
+    // same time (the memory latency of one hides behind the other's) and are one phase apart again afterwards.
+    // Without the two barriers the phase barriers alone would let one group's epilogue run while the other
+    // group waits, one after the other.
+    // (The SwiGLU epilogue stages two outputs at once and keeps its two slots per wave; its groups still run
+    // one after the other.)
+    constexpr bool BOTH_EPI = EPI != EPI_SWIGLU;  // both groups' epilogues at the same time
+    if (BOTH_EPI && !grp_y) phase_end();
     // (The lane index goes through an empty asm statement: otherwise the compiler computes the epilogue's
     // per-lane addresses once, ahead of the tile loop, and they occupy dozens of registers in the main loop.)
     int elane = lane;
@@ -536,8 +545,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       // two panels of the step just finished.
       const bool interior = cc.w.m0 + BM <= cM && cc.w.n0 + BN <= cN;
       if (interior && !accumulate && cc.nsteps != 0) {
-        char* const fslot[2] = {grp_y ? ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024
-                                      : ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024,
+        // (the late waves have already refilled their units of the A panel's slot: they have one slot, and
+        // write a block into it only after the block before has been read back)
+        char* const fslot[2] = {ring + slot_add(sa, grp_y ? NSLOT - 1 : NSLOT - 2) * PANEL + unit0 * 1024,
                                 ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024};
         const int er = elane & 31, esw = (er >> 1) & 7, rrow = elane >> 3, rchunk = elane & 7;
         const uint32_t voff = (uint32_t)(rrow * cld + rchunk * 4) * 4u;
@@ -553,10 +563,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
             for (int q = 0; q < 4; ++q) c[r * 4 + q] = 0.f;
           }
         };
-        put(0);
+        if (!grp_y) put(0);
 #pragma unroll
         for (int b = 0; b < MI * NI; ++b) {
-          if (b + 1 < MI * NI) put(b + 1);
+          if (grp_y) put(b);
+          else if (b + 1 < MI * NI) put(b + 1);
           char* slot = fslot[b & 1];
 #pragma unroll
           for (int it = 0; it < 4; ++it) {
@@ -599,10 +610,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       // the epilogue.  LDS serves one wave's accesses in program order.
       static_assert(NI % 2 == 0, "staged epilogue: 64-column units");
       constexpr int NJP = NI / 2, NU = MI * NJP;
-      // (the late waves have already refilled their units of the A panel's slot: they take their SIMD
-      // partner's units of the B panel's slot, which the partner stopped using a phase ago)
-      char* const slot0 = grp_y ? ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024
-                                : ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024;
+      // (the late waves have already refilled their units of the A panel's slot: their two slots are one and
+      // the same, so everything below writes a slot only after what it held has been read back, in program
+      // order)
+      // (SwiGLU, groups one after the other: the late waves take their SIMD partner's units of the B panel's
+      // slot, which the partner stopped using a phase ago)
+      char* const slot0 = !grp_y ? ring + slot_add(sa, NSLOT - 2) * PANEL + unit0 * 1024
+                          : BOTH_EPI ? ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024
+                                     : ring + slot_add(sa, NSLOT - 1) * PANEL + (unit0 - Cfg::NWAVES / 2 * UPW) * 1024;
       char* const slot1 = ring + slot_add(sa, NSLOT - 1) * PANEL + unit0 * 1024;
       const int er = elane & 31, esw = (er >> 1) & 7;
       const int rrow = elane >> 3, rchunk = elane & 7;
@@ -759,19 +774,29 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 #pragma unroll
           for (int u = 0; u < NU; ++u) {
             const int i = u / NJP, j0 = 2 * (u % NJP);
+            // rows 0-15 of the unit are staged in slot 0, rows 16-31 in slot 1: the early waves write both at
+            // once, the late waves (one slot) the second half after the first has been read back
+            auto stage_half = [&](int half) {
+              if ((er >> 4) == half) {
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
+                for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                f32x16& c = acc[0][i][j0 + jj];
-                const f32x4 v = {c[r * 4], c[r * 4 + 1], c[r * 4 + 2], c[r * 4 + 3]};
-                *reinterpret_cast<f32x4*>(frow(er) + (((jj * 8 + 2 * r + ekhalf) ^ (er & 15)) << 4)) = v;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) c[r * 4 + q] = 0.f;
+                  for (int r = 0; r < 4; ++r) {
+                    const f32x16& c = acc[0][i][j0 + jj];
+                    const f32x4 v = {c[r * 4], c[r * 4 + 1], c[r * 4 + 2], c[r * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(frow(er) + (((jj * 8 + 2 * r + ekhalf) ^ (er & 15)) << 4)) = v;
+                  }
               }
+            };
+            stage_half(0);
+            if (!grp_y) stage_half(1);
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
               __builtin_amdgcn_sched_barrier(0);  // (keeps the compiler from hoisting the address arithmetic of all rows: registers are short here)
+              if (it == 2 && grp_y) {
+                stage_half(1);
+                __builtin_amdgcn_sched_barrier(0);
+              }
               f32x4 dhr[2];
               {
                 const int rr = it * 8 + rrow;
@@ -806,6 +831,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       }
     }
     zero_acc();
+    if (BOTH_EPI && grp_y) phase_end();
     cc.w.tile = tile_of_round(first_tile, ++cc.w.round);
     open_c();
   }
