@@ -112,5 +112,36 @@ def build(extra_flags=(), verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_sanitized(out_dir: str, driver_c: str) -> str:
+    """Builds, into out_dir, a copy of the library whose api.hip HOST code is instrumented with AddressSanitizer and
+    UndefinedBehaviorSanitizer (the device code and the other two objects are the ordinary ones: build() first),
+    and the C program driver_c against it with the same sanitizers.  Returns the path of the program."""
+    os.makedirs(out_dir, exist_ok=True)
+    san = []
+    for f in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"):
+        san += ["-Xarch_host", f]
+    flags = [f for f in FLAGS if f != "-Rpass-analysis=kernel-resource-usage"]
+    obj = os.path.join(out_dir, "api_san.o")
+    lib = os.path.join(out_dir, "libmodse_hostsan.so")
+    exe = os.path.join(out_dir, "host_abi_driver")
+    others = [os.path.join(CSRC, s.replace(".hip", ".o")) for s in SOURCES if s != "api.hip"]
+    for o in others:
+        if not os.path.exists(o):
+            raise FileNotFoundError(f"{o} not found: run build() first")
+    steps = [
+        [_hipcc(), *flags, *san, "-g", "-c", os.path.join(CSRC, "api.hip"), "-o", obj],
+        [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *san, obj, *others, "-o", lib],
+        [_hipcc(), "-x", "c", "-std=c99", "-g", "-fsanitize=address", "-fsanitize=undefined",
+         "-fno-sanitize-recover=undefined", "-I" + os.path.join(ROOT, "include"), driver_c, "-x", "none", lib,
+         "-Wl,-rpath," + out_dir, "-o", exe],
+    ]
+    for cmd in steps:
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+            raise RuntimeError("sanitized host build failed: " + " ".join(cmd) + "\n" + err)
+    return exe
+
+
 if __name__ == "__main__":
     build(sys.argv[1:])

@@ -23,7 +23,12 @@ size_t esize_of(modse_dtype dt) { return dt == MODSE_F32 ? 4 : 2; }
 modse_status check_desc(const modse_desc* desc, int64_t T) {
   if (!desc || !desc->d_ff) return MODSE_ERR_INVALID_ARG;
   if (T < 0) return MODSE_ERR_INVALID_ARG;
-  if (desc->dtype != MODSE_F32 && desc->dtype != MODSE_BF16) return MODSE_ERR_UNSUPPORTED;
+  // (the field is read as an integer: a caller may have put any value there, and loading a value that is none of
+  // the enumerators through the enumeration type is undefined)
+  static_assert(sizeof(modse_dtype) == sizeof(int32_t), "enumeration stored as a 32-bit integer");
+  int32_t dtype_bits;
+  std::memcpy(&dtype_bits, &desc->dtype, sizeof dtype_bits);
+  if (dtype_bits != (int32_t)MODSE_F32 && dtype_bits != (int32_t)MODSE_BF16) return MODSE_ERR_UNSUPPORTED;
   if (desc->n_experts < 1 || desc->d_model < 1) return MODSE_ERR_INVALID_ARG;
   if (desc->top_k < 1 || desc->top_k > desc->n_experts) return MODSE_ERR_INVALID_ARG;
   if (desc->n_experts > MODSE_MAX_EXPERTS) return MODSE_ERR_UNSUPPORTED;
@@ -256,7 +261,10 @@ GateExtPtrs ext_ptrs(const modse_gate_ext* e) {
 extern "C" {
 
 const char* modse_status_string(modse_status s) {
-  switch (s) {
+  int32_t code;  // (read as an integer: a C caller may pass any value)
+  static_assert(sizeof(modse_status) == sizeof(int32_t), "enumeration stored as a 32-bit integer");
+  std::memcpy(&code, &s, sizeof code);
+  switch (code) {
     case MODSE_OK: return "ok";
     case MODSE_ERR_INVALID_ARG: return "invalid argument";
     case MODSE_ERR_UNSUPPORTED: return "unsupported configuration";
