@@ -203,7 +203,7 @@ modse_status modse_routing_stats(const modse_desc* desc, int64_t T, const modse_
  * (HOST array of MODSE_N_STAGES floats; stages not run read 0). */
 enum {
   MODSE_STAGE_ROUTE = 0,    /* router GEMM + top-k + gate (+ auxiliary loss) */
-  MODSE_STAGE_PERMUTE = 1,  /* histogram, scan over blocks, stable row scatter */
+  MODSE_STAGE_PERMUTE = 1,  /* histogram, scan over blocks (+ the tile plans of the forward GEMMs), stable row scatter */
   MODSE_STAGE_UP = 2,       /* grouped W1/W3 GEMM + SwiGLU */
   MODSE_STAGE_DOWN = 3,     /* grouped W2 GEMM */
   MODSE_STAGE_COMBINE = 4,  /* gate-weighted unpermute */
@@ -211,8 +211,7 @@ enum {
   MODSE_STAGE_BWD_DGRAD = 6,/* dH (+SwiGLU backward) and dX_permuted GEMMs */
   MODSE_STAGE_BWD_WGRAD = 7,/* dW1, dW3, dW2 GEMMs */
   MODSE_STAGE_BWD_ROUTER = 8,/* dX gather, d logits, dW_gate */
-  MODSE_STAGE_PLAN = 9,     /* device-side tile plans of the two forward GEMMs */
-  MODSE_N_STAGES = 10
+  MODSE_N_STAGES = 9
 };
 modse_status modse_stage_timing_enable(int on);
 modse_status modse_stage_times(float* ms);

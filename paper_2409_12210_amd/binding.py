@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 MODSE_F32, MODSE_BF16 = 0, 1
-STAGES = ("route", "permute", "up", "down", "combine", "bwd_prep", "bwd_dgrad", "bwd_wgrad", "bwd_router", "plan")
+STAGES = ("route", "permute", "up", "down", "combine", "bwd_prep", "bwd_dgrad", "bwd_wgrad", "bwd_router")
 
 
 class ModseError(RuntimeError):

@@ -421,14 +421,10 @@ modse_status modse_layer_fwd_ext(const modse_desc* desc, int64_t T, const void* 
   const int kchunk = saved ? 0 : splitk_chunk(L);
   pa.kchunk = kchunk;
   pa.Opart = reinterpret_cast<float*>(wsb + w.Opart);
-  // histogram, scan, stable scatter, then the tile plans (one launch for all of it on decode-sized batches,
-  // which then shows under MODSE_STAGE_PERMUTE alone)
-  HIP_TRY(launch_permute(L, dt, x, R, RB, Xp, ext ? &G : nullptr, T <= MODSE_PERMUTE_SMALL_MAX_T ? &pa : nullptr, s));
+  // histogram, scan (which also writes the tile plans), stable scatter: one launch for all of it on decode-sized
+  // batches
+  HIP_TRY(launch_permute(L, dt, x, R, RB, Xp, ext ? &G : nullptr, &pa, s));
   stamp.mark(MODSE_STAGE_PERMUTE);
-  if (T > MODSE_PERMUTE_SMALL_MAX_T) {
-    HIP_TRY(launch_plan_fwd(L, dt, R.counts, R.offsets, pa, s));
-    stamp.mark(MODSE_STAGE_PLAN);
-  }
 
   const int skinny = T <= MODSE_SKINNY_TOKENS;
   HIP_TRY(launch_grouped_gemm(dt, EPI_SWIGLU, pa.up, 0, saved != nullptr, tiles_bound(L, T, pa.up_tile, true), s, -1,

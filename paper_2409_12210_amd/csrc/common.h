@@ -158,7 +158,7 @@ inline size_t route_wpad_bytes(const LayerDims& L, size_t elem_size) {
 hipError_t launch_router(const LayerDims& L, modse_dtype dt, const void* x, const void* W_gate, const float* bias,
                          const RoutingPtrs& R, const RouteBufs& B, const GateExtPtrs* G, hipStream_t s);
 struct FwdPlanArgs;
-// plan != null: also makes the tile plans of the two forward GEMMs (batches of at most
+// plan != null: the scan launch also makes the tile plans of the two forward GEMMs (batches of at most
 // MODSE_PERMUTE_SMALL_MAX_T tokens do all of this in one launch)
 hipError_t launch_permute(const LayerDims& L, modse_dtype dt, const void* x, const RoutingPtrs& R, const RouteBufs& B,
                           void* Xp, const GateExtPtrs* G, const FwdPlanArgs* plan, hipStream_t s);
@@ -203,8 +203,6 @@ struct FwdPlanArgs {
   GemmPlan *up, *down;
   TileShape up_tile, down_tile;
 };
-hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
-                           const FwdPlanArgs& a, hipStream_t s);
 
 struct BwdPlanArgs {
   const void *Xp, *dO, *H, *dHdA, *dHdB;

@@ -95,14 +95,9 @@ __global__ __launch_bounds__(256) void gg_f32_kernel(const GemmPlan* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------------
-// plan kernels (single block): device-side counts -> problem tables
+// plan kernel of the backward GEMMs (single block): device-side counts -> problem tables.  (The forward plans
+// are made by the routing stage's scan launch, see gemm_plan.h.)
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void plan_fwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
-                                                      const int32_t* __restrict__ offsets, FwdPlanArgs a) {
-  __shared__ int s_tiles[MODSE_MAX_PROBLEMS];
-  plan_fwd_body(L, esize, counts, offsets, a, s_tiles);
-}
-
 __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, const int32_t* __restrict__ counts,
                                                       const int32_t* __restrict__ offsets, BwdPlanArgs a) {
   __shared__ int s_tiles[MODSE_MAX_PROBLEMS];
@@ -251,12 +246,6 @@ hipError_t launch_grouped_gemm(modse_dtype dt, int epilogue, const GemmPlan* pla
       return run_bf16<256, 256, 1, 4, 2, EPI_STORE_F32, LAYOUT_AB_K>(plan, accumulate, save_pre, max_tiles, s);
   }
   return hipErrorInvalidValue;
-}
-
-hipError_t launch_plan_fwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,
-                           const FwdPlanArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(plan_fwd_kernel, dim3(1), dim3(64), 0, s, L, dt == MODSE_F32 ? 4 : 2, counts, offsets, a);
-  return hipGetLastError();
 }
 
 hipError_t launch_plan_bwd(const LayerDims& L, modse_dtype dt, const int32_t* counts, const int32_t* offsets,

@@ -572,64 +572,101 @@ __global__ __launch_bounds__(64) void route_hist_kernel(const int32_t* __restric
   for (int i = tid; i <= N; i += 64) blockhist[(size_t)blockIdx.x * (N + 1) + i] = s_hist[i];
 }
 
-// Single block.  Turns blockhist[b][e] into the exclusive prefix over blocks (in place) and writes
-// counts, offsets and the near-tie total.  Each thread owns a contiguous run of blocks; the 256 run totals
-// of one expert are scanned by the first wave.
+// Single block.  Turns blockhist[b][e] into the exclusive prefix over blocks (in place), writes counts, offsets
+// and the near-tie total and, when a forward pass follows, the tile plans of its two GEMMs (from the counts
+// still in LDS: no second launch, no round trip through memory).  Each thread owns a contiguous run of blocks.
+// Up to SCAN_EC expert columns are handled at once and a thread's blocks four at a time, so that the loads of
+// a step are all in flight together (the launch is a chain of memory latencies and nothing else); the 256 run
+// totals of a column are scanned by one wave.
+constexpr int SCAN_EC = 16, SCAN_NB = 4;
 __global__ __launch_bounds__(256) void route_scan_kernel(int32_t* __restrict__ blockhist, int nb, int N,
                                                          int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                                         int32_t* __restrict__ near_tie_count) {
-  __shared__ int s_part[256];
+                                                         int32_t* __restrict__ near_tie_count, LayerDims L, int esize,
+                                                         FwdPlanArgs plan, int with_plan) {
+  __shared__ int s_part[SCAN_EC][256];
   __shared__ int s_total[MODSE_MAX_EXPERTS + 1];
-  const int tid = threadIdx.x;
+  __shared__ int s_counts[MODSE_MAX_EXPERTS], s_offsets[MODSE_MAX_EXPERTS + 1];
+  __shared__ int s_tiles[MODSE_MAX_PROBLEMS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per = (nb + 255) / 256;
   const int b0 = min(tid * per, nb), b1 = min(b0 + per, nb);
   const int W = N + 1;
-  for (int e = 0; e < W; ++e) {
-    int sum = 0;
-    for (int b = b0; b < b1; ++b) sum += blockhist[(size_t)b * W + e];
-    s_part[tid] = sum;
+  for (int e0 = 0; e0 < W; e0 += SCAN_EC) {
+    const int ne = min(SCAN_EC, W - e0);
+    int sum[SCAN_EC];
+#pragma unroll
+    for (int j = 0; j < SCAN_EC; ++j) sum[j] = 0;
+    for (int b = b0; b < b1; b += SCAN_NB) {
+      int v[SCAN_NB][SCAN_EC];
+#pragma unroll
+      for (int q = 0; q < SCAN_NB; ++q)
+#pragma unroll
+        for (int j = 0; j < SCAN_EC; ++j)
+          v[q][j] = (b + q < b1 && j < ne) ? blockhist[(size_t)(b + q) * W + e0 + j] : 0;
+#pragma unroll
+      for (int q = 0; q < SCAN_NB; ++q)
+#pragma unroll
+        for (int j = 0; j < SCAN_EC; ++j) sum[j] += v[q][j];
+    }
+#pragma unroll
+    for (int j = 0; j < SCAN_EC; ++j) s_part[j][tid] = sum[j];
     __syncthreads();
-    if (tid < 64) {
+    for (int j = wave; j < ne; j += 4) {  // exclusive scan of column j's 256 run totals
       int v[4], local = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        v[i] = s_part[tid * 4 + i];
+        v[i] = s_part[j][lane * 4 + i];
         local += v[i];
       }
       int incl = local;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const int up = __shfl_up(incl, o, 64);
-        if (tid >= o) incl += up;
+        if (lane >= o) incl += up;
       }
       int run = incl - local;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        s_part[tid * 4 + i] = run;
+        s_part[j][lane * 4 + i] = run;
         run += v[i];
       }
-      if (tid == 63) s_total[e] = incl;
+      if (lane == 63) s_total[e0 + j] = incl;
     }
     __syncthreads();
-    if (e < N) {
-      int run = s_part[tid];
-      for (int b = b0; b < b1; ++b) {
-        const int v = blockhist[(size_t)b * W + e];
-        blockhist[(size_t)b * W + e] = run;
-        run += v;
-      }
+    int run[SCAN_EC];
+#pragma unroll
+    for (int j = 0; j < SCAN_EC; ++j) run[j] = s_part[j][tid];
+    for (int b = b0; b < b1; b += SCAN_NB) {  // (the near-tie column, e == N, keeps its counts)
+      int v[SCAN_NB][SCAN_EC];
+#pragma unroll
+      for (int q = 0; q < SCAN_NB; ++q)
+#pragma unroll
+        for (int j = 0; j < SCAN_EC; ++j)
+          v[q][j] = (b + q < b1 && e0 + j < N) ? blockhist[(size_t)(b + q) * W + e0 + j] : 0;
+#pragma unroll
+      for (int q = 0; q < SCAN_NB; ++q)
+#pragma unroll
+        for (int j = 0; j < SCAN_EC; ++j)
+          if (b + q < b1 && e0 + j < N) {
+            blockhist[(size_t)(b + q) * W + e0 + j] = run[j];
+            run[j] += v[q][j];
+          }
     }
     __syncthreads();
   }
   if (tid == 0) {
     int run = 0;
     for (int e = 0; e < N; ++e) {
-      counts[e] = s_total[e];
-      offsets[e] = run;
+      counts[e] = s_counts[e] = s_total[e];
+      offsets[e] = s_offsets[e] = run;
       run += s_total[e];
     }
-    offsets[N] = run;
+    offsets[N] = s_offsets[N] = run;
     near_tie_count[0] = s_total[N];
+  }
+  if (with_plan) {
+    __syncthreads();
+    modse_gemm::plan_fwd_body(L, esize, s_counts, s_offsets, plan, s_tiles);
   }
 }
 
@@ -1245,8 +1282,8 @@ hipError_t router_typed(const LayerDims& L, const void* xv, const void* Wgv, con
   return e;
 }
 
-// histogram (where the router has not made it), scan over blocks, stable scatter; batches of at most
-// PERMUTE_SMALL_MAX_T tokens: one fused launch, which also makes the forward tile plans when `plan` is given
+// histogram (where the router has not made it), scan over blocks (which also makes the forward tile plans when
+// `plan` is given), stable scatter; batches of at most PERMUTE_SMALL_MAX_T tokens: one fused launch for all of it
 template <typename T>
 hipError_t permute_typed(const LayerDims& L, modse_dtype dt, const void* xv, const RoutingPtrs& R, const RouteBufs& B,
                          void* Xpv, const GateExtPtrs* G, const FwdPlanArgs* plan, hipStream_t s) {
@@ -1266,13 +1303,11 @@ hipError_t permute_typed(const LayerDims& L, modse_dtype dt, const void* xv, con
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(256), 0, s, B.blockhist, nb, L.N, R.counts, R.offsets,
-                     R.near_tie_count);
+                     R.near_tie_count, L, dt == MODSE_F32 ? 4 : 2, plan ? *plan : FwdPlanArgs{}, plan ? 1 : 0);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((scatter_kernel<T>), dim3(nb), dim3(ROUTE_THREADS), 0, s, x, L.T, L.d, L.N, L.k, R.topk_idx,
                      R.offsets, B.blockhist, R.row_of, R.src_of, static_cast<T*>(Xpv));
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (plan) e = launch_plan_fwd(L, dt, R.counts, R.offsets, *plan, s);
-  return e;
+  return hipGetLastError();
 }
 
 // dX and the gradient of one router-side matrix, 8 expert columns per launch

@@ -52,7 +52,8 @@ def test_every_built_kernel_is_within_the_register_budget():
     assert len(rows) >= 60                                   # every instantiation of every kernel is listed
     names = " ".join(r[0] for r in rows)
     for k in ("router_stream_kernel", "router_kernel", "router_token_kernel", "scatter_kernel", "combine_kernel",
-              "bwd_gate_rows_kernel", "gg_bf16_kernel", "gg_bf16_skinny_kernel", "gg_f32_kernel", "plan_fwd_kernel"):
+              "bwd_gate_rows_kernel", "gg_bf16_kernel", "gg_bf16_skinny_kernel", "gg_f32_kernel", "plan_bwd_kernel",
+              "route_scan_kernel"):
         assert k in names, k
     for name, vgprs, agprs, scratch, spill, occupancy, lds in rows:
         assert int(scratch) == 0 and int(spill) == 0 and int(agprs) == 0, name
