@@ -81,6 +81,9 @@ ROUTE_CASES = [
     ("stream_n64_bf16", 96, (32,) * 64, 1025, "bf16", 2),
     ("stream_ragged_d", 1120, (64, 192, 128, 128), 4100, "bf16", 2),
     ("stream_many_groups", 32, (32,) * 8, 40000, "bf16", 2),
+    # scan over more than 4 blocks per thread, with one and with several 16-column steps
+    ("scan_long_runs", 32, (32,) * 8, 140001, "bf16", 2),
+    ("scan_long_runs_n40", 32, (32,) * 40, 35001, "f32", 2),
     # more than 16 experts on a small batch, and an expert count that is not a power of two: the router that
     # reads (a padded copy of) W_gate from memory
     ("block_n24", 64, (32,) * 24, 300, "bf16", 2),
