@@ -696,7 +696,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
       } else if constexpr (EPI == EPI_SWIGLU) {
         // h = silu(a) b and the saved term p = dh/da go to the slots four columns at a time; q = dh/db
         // takes b's place in the accumulator and follows once the slot of h is free
-        auto swiglu_unit = [&](int u) {
+        // (an inference pass, which saves nothing, takes the copy of the code without the arithmetic of p)
+        auto swiglu_unit = [&](int u, auto save_tag) {
+          constexpr bool SAVE = decltype(save_tag)::value;
           const int i = u / NJP, j0 = 2 * (u % NJP);
 #pragma unroll
           for (int jj = 0; jj < 2; ++jj)
@@ -706,42 +708,51 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gg_bf16_kernel(const Ge
 #pragma unroll
               for (int q4 = 0; q4 < 4; ++q4) {
                 const float a = acc[0][i][j0 + jj][r * 4 + q4], b = acc[1][i][j0 + jj][r * 4 + q4];
-                float h, p, q;
-                swiglu_terms(a, b, sigmoid_fast(a), h, p, q);
-                hv[q4] = (bf16_t)h;
-                pv[q4] = (bf16_t)p;
-                acc[1][i][j0 + jj][r * 4 + q4] = q;
+                if constexpr (SAVE) {
+                  float h, p, q;
+                  swiglu_terms(a, b, sigmoid_fast(a), h, p, q);
+                  hv[q4] = (bf16_t)h;
+                  pv[q4] = (bf16_t)p;
+                  acc[1][i][j0 + jj][r * 4 + q4] = q;
+                } else {
+                  hv[q4] = (bf16_t)(a * sigmoid_fast(a) * b);
+                }
               }
               *acc_pos(slot0, jj, r) = hv;
-              if (save_pre) *acc_pos(slot1, jj, r) = pv;
+              if constexpr (SAVE) *acc_pos(slot1, jj, r) = pv;
             }
         };
-        if (interior) {
+        auto swiglu_tile = [&](auto save_tag) {
+          constexpr bool SAVE = decltype(save_tag)::value;
+          if (interior) {
 #pragma unroll
-          for (int u = 0; u < NU; ++u) {
-            const int i = u / NJP, j0 = 2 * (u % NJP);
-            swiglu_unit(u);
-            store_unit_interior(slot0, u, cc.C + wave_off);
-            if (save_pre) {
-              store_unit_interior(slot1, u, cc.C2 + wave_off);
-              put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
-              store_unit_interior(slot0, u, cc.C3 + wave_off);
+            for (int u = 0; u < NU; ++u) {
+              const int i = u / NJP, j0 = 2 * (u % NJP);
+              swiglu_unit(u, save_tag);
+              store_unit_interior(slot0, u, cc.C + wave_off);
+              if constexpr (SAVE) {
+                store_unit_interior(slot1, u, cc.C2 + wave_off);
+                put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
+                store_unit_interior(slot0, u, cc.C3 + wave_off);
+              }
+            }
+          } else {
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+              if (unit_m(u) >= cM) continue;
+              const int i = u / NJP, j0 = 2 * (u % NJP);
+              swiglu_unit(u, save_tag);
+              store_unit(slot0, u, cc.C);
+              if constexpr (SAVE) {
+                store_unit(slot1, u, cc.C2);
+                put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
+                store_unit(slot0, u, cc.C3);
+              }
             }
           }
-        } else {
-#pragma unroll
-          for (int u = 0; u < NU; ++u) {
-            if (unit_m(u) >= cM) continue;
-            const int i = u / NJP, j0 = 2 * (u % NJP);
-            swiglu_unit(u);
-            store_unit(slot0, u, cc.C);
-            if (save_pre) {
-              store_unit(slot1, u, cc.C2);
-              put_unit(slot0, acc[1][i][j0], acc[1][i][j0 + 1]);
-              store_unit(slot0, u, cc.C3);
-            }
-          }
-        }
+        };
+        if (save_pre) swiglu_tile(std::true_type{});
+        else swiglu_tile(std::false_type{});
       } else if constexpr (EPI == EPI_SWIGLU_BWD) {
         {
           // dh goes through LDS as float32, one unit (32 rows x 64 columns, 8 KiB = both slots) at a time:
