@@ -81,6 +81,17 @@ ROUTE_CASES = [
     ("stream_n64_bf16", 96, (32,) * 64, 1025, "bf16", 2),
     ("stream_ragged_d", 1120, (64, 192, 128, 128), 4100, "bf16", 2),
     ("stream_many_groups", 32, (32,) * 8, 40000, "bf16", 2),
+    # the same router on the float64 matrix instruction (d a multiple of 256, at most 16 experts): both padded
+    # expert counts, expert counts that are no multiple of 4, both dtypes, k = 1, ragged token counts, several
+    # groups per workgroup, and a matrix that is one size too large for it (the vector form takes over)
+    ("mfma_n3", 256, (32, 64, 96), 4111, "bf16", 2),
+    ("mfma_n5_f32", 512, (32,) * 5, 4500, "f32", 2),
+    ("mfma_n12", 256, (32,) * 12, 4200, "bf16", 2),
+    ("mfma_n16_f32_top1", 512, (32,) * 16, 5001, "f32", 1),
+    ("mfma_many_groups", 256, (32,) * 8, 40001, "bf16", 2),
+    ("mfma_d768", 768, (64,) * 8, 4097, "bf16", 2),
+    ("mfma_d2048", 2048, (32,) * 8, 4160, "bf16", 2),
+    ("mfma_too_large_n16_d1024", 1024, (32,) * 16, 4100, "bf16", 2),
     # scan over more than 4 blocks per thread, with one and with several 16-column steps
     ("scan_long_runs", 32, (32,) * 8, 140001, "bf16", 2),
     ("scan_long_runs_n40", 32, (32,) * 40, 35001, "f32", 2),
@@ -110,15 +121,16 @@ def test_route_with_bias_and_empty_expert():
     assert got["counts"][2] == 0 and got["counts"][4] > 300
 
 
-@pytest.mark.parametrize("T", [50, 5000], ids=["token_router", "stream_router"])
-def test_route_masked_experts_second_pick_differs_from_first(T):
+@pytest.mark.parametrize("T,d", [(50, 128), (5000, 128), (5000, 256)],
+                         ids=["token_router", "stream_router", "mfma_router"])
+def test_route_masked_experts_second_pick_differs_from_first(T, d):
     # every expert but one masked out by an infinite negative bias: the second pick is the lowest other index
     # (as in a stable descending sort) with gate weight 0, never a repeat of the first
     from oracle import modse_oracle as orc2
     for keep in (0, 5):
         bias = np.full(8, -np.inf, dtype=np.float32)
         bias[keep] = 0.0
-        inp = make("masked", 128, (64,) * 8, T, "f32", bias=bias, seed=9 + keep)
+        inp = make("masked", d, (64,) * 8, T, "f32", bias=bias, seed=9 + keep)
         r = _runner(inp)
         r.route()
         got = r.routing_host()
