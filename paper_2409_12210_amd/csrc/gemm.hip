@@ -120,9 +120,10 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
     P.E2 = cadd(a.dHdB, hoff * es);
     P.M = n_e; P.N = f; P.K = d;
     P.lda = d; P.ldb = f; P.ldc = f;
+    s_tiles[i] = set_tiles(P, a.dh_tile.bm, a.dh_tile.bn);
     a.dh->prob[i] = P;
   }
-  finish_plan(a.dh, i, L.N, a.dh_tile.bm, a.dh_tile.bn, s_tiles);
+  finish_plan(a.dh, i, L.N, s_tiles);
   if (on) {  // dXp = dA W1 + dB W3 (W1_e, W3_e are [f, d]: [K, N] operands)
     GemmProblem P = {};
     P.A = cadd(a.dA, hoff * es);
@@ -132,9 +133,10 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
     P.C = vadd(a.dXp, roff * es);
     P.M = n_e; P.N = d; P.K = f;
     P.lda = f; P.ldb = d; P.ldc = d;
+    s_tiles[i] = set_tiles(P, a.dx_tile.bm, a.dx_tile.bn);
     a.dx->prob[i] = P;
   }
-  finish_plan(a.dx, i, L.N, a.dx_tile.bm, a.dx_tile.bn, s_tiles);
+  finish_plan(a.dx, i, L.N, s_tiles);
   // Weight gradients contract over the expert's tokens, so a tile costs n_e K-steps whatever its expert's
   // width: the three GEMMs of one expert are listed together, experts by falling token count.
   if (on) {
@@ -147,6 +149,7 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
       P.C = (which ? a.dW3 : a.dW1) + woff;
       P.M = f; P.N = d; P.K = n_e;
       P.lda = f; P.ldb = d; P.ldc = d;
+      s_tiles[3 * rank + which] = set_tiles(P, a.wg_tile.bm, a.wg_tile.bn);
       a.wg->prob[3 * rank + which] = P;
     }
     GemmProblem P = {};  // dW2 = dO^T H
@@ -155,9 +158,10 @@ __global__ __launch_bounds__(64) void plan_bwd_kernel(LayerDims L, int esize, co
     P.C = a.dW2 + woff;
     P.M = d; P.N = f; P.K = n_e;
     P.lda = d; P.ldb = f; P.ldc = f;
+    s_tiles[3 * rank + 2] = set_tiles(P, a.wg_tile.bm, a.wg_tile.bn);
     a.wg->prob[3 * rank + 2] = P;
   }
-  finish_plan(a.wg, i, 3 * L.N, a.wg_tile.bm, a.wg_tile.bn, s_tiles);
+  finish_plan(a.wg, i, 3 * L.N, s_tiles);
 }
 
 int num_cus() {

@@ -7,17 +7,19 @@
 
 namespace modse_gemm {
 
-// Every thread has written its problems (n in total); fills in the tile counts and the tile prefix.
-__device__ inline void finish_plan(GemmPlan* plan, int i, int n, int bm, int bn, int* s_tiles) {
-  __syncthreads();
-  for (int q = i; q < n; q += blockDim.x) {
-    GemmProblem& P = plan->prob[q];
-    P.mtiles = (P.M + bm - 1) / bm;
-    P.ntiles = (P.N + bn - 1) / bn;
-    s_tiles[q] = P.mtiles * P.ntiles;
-    P.magic_group = tile_magic((uint32_t)(GROUP_M * P.ntiles), (uint64_t)s_tiles[q]);
-    P.magic_tail = tile_magic((uint32_t)(P.mtiles % GROUP_M), (uint64_t)GROUP_M * P.ntiles);
-  }
+// Tile counts and decode constants of a problem (from the fields in registers, before the problem is stored);
+// returns its number of tiles.
+__device__ inline int set_tiles(GemmProblem& P, int bm, int bn) {
+  P.mtiles = (P.M + bm - 1) / bm;
+  P.ntiles = (P.N + bn - 1) / bn;
+  const int tiles = P.mtiles * P.ntiles;
+  P.magic_group = tile_magic((uint32_t)(GROUP_M * P.ntiles), (uint64_t)tiles);
+  P.magic_tail = tile_magic((uint32_t)(P.mtiles % GROUP_M), (uint64_t)GROUP_M * P.ntiles);
+  return tiles;
+}
+
+// Every thread has stored its problems (n in total) and left their tile counts in s_tiles; fills in the tile prefix.
+__device__ inline void finish_plan(GemmPlan* plan, int i, int n, int* s_tiles) {
   __syncthreads();
   if (i == 0) {
     int run = 0;
@@ -55,9 +57,10 @@ __device__ inline void plan_fwd_body(const LayerDims& L, int esize, const int32_
     P.C3 = vadd(a.dHdB, hoff * es);
     P.M = n_e; P.N = f; P.K = d;
     P.lda = d; P.ldb = d; P.ldc = f;
+    s_tiles[i] = set_tiles(P, a.up_tile.bm, a.up_tile.bn);
     a.up->prob[i] = P;
   }
-  finish_plan(a.up, i, L.N, a.up_tile.bm, a.up_tile.bn, s_tiles);
+  finish_plan(a.up, i, L.N, s_tiles);
   if (a.kchunk > 0) {  // split-K: one problem per (expert, chunk of K), float32 partial sums
     int first = 0;     // problems of the experts listed before this one
     for (int q = 0; q < i && q < L.N; ++q) first += (L.f[L.order[q]] + a.kchunk - 1) / a.kchunk;
@@ -73,10 +76,11 @@ __device__ inline void plan_fwd_body(const LayerDims& L, int esize, const int32_
         P.C = a.Opart + ((size_t)c * L.T * L.k + offsets[e]) * d;
         P.M = n_e; P.N = d; P.K = min(a.kchunk, f - k0);
         P.lda = f; P.ldb = f; P.ldc = d;
+        s_tiles[first + c] = set_tiles(P, a.down_tile.bm, a.down_tile.bn);
         a.down->prob[first + c] = P;
       }
     }
-    finish_plan(a.down, i, total, a.down_tile.bm, a.down_tile.bn, s_tiles);
+    finish_plan(a.down, i, total, s_tiles);
     return;
   }
   if (on) {
@@ -86,9 +90,10 @@ __device__ inline void plan_fwd_body(const LayerDims& L, int esize, const int32_
     P.C = vadd(a.O, (size_t)offsets[e] * d * es);
     P.M = n_e; P.N = d; P.K = f;
     P.lda = f; P.ldb = f; P.ldc = d;
+    s_tiles[i] = set_tiles(P, a.down_tile.bm, a.down_tile.bn);
     a.down->prob[i] = P;
   }
-  finish_plan(a.down, i, L.N, a.down_tile.bm, a.down_tile.bn, s_tiles);
+  finish_plan(a.down, i, L.N, s_tiles);
 }
 
 }  // namespace modse_gemm
